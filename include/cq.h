@@ -1,0 +1,158 @@
+/*
+ * cq.h - C ABI of the CalibQuant hot path on MI355X (gfx950).
+ *
+ * Two operations of arxiv 2502.14882:
+ *   cq_quantize_kv   uniform b-bit quantization of the visual-token KV cache
+ *                    (Sec. 2.2 quantize equation; Sec. 3.1 channel-wise statistics;
+ *                    packing appendix), producing packed codes + scale + min;
+ *   cq_decode_attn   one decode step of attention that reads the packed cache
+ *                    directly (Sec. 3.1 post-scaling, Sec. 3.2 calibration g,
+ *                    Sec. 2.1 softmax(.)V), with the 16-bit text-token tail of
+ *                    Sec. 3 / Sec. 3.3 ("irregular matrix shape") merged into the
+ *                    same softmax.
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or keeps device memory; it only enqueues kernels.
+ *   - All tensors are dense and contiguous in the stated layout, channel (head
+ *     dimension) fastest, and 16-byte aligned.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream).  The host structs are read before the call returns.
+ *   - Return value: CQ_OK (0) or a negative cq_status.  Argument errors are found on
+ *     the host before any HIP call, so nothing is launched when one is returned.
+ *     cq_last_error() gives a message for the last failure on the calling thread.
+ *   - Inputs must be finite; NaN/Inf behaviour is undefined (the paper is silent).
+ *   - Query head hq attends to KV head hq / (n_q_heads / n_kv_heads).
+ */
+#ifndef CQ_H_
+#define CQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CQ_OK = 0,
+  CQ_ERR_NULL = -1,        /* a required pointer is NULL */
+  CQ_ERR_SHAPE = -2,       /* sizes do not divide / are out of range */
+  CQ_ERR_UNSUPPORTED = -3, /* bits, axis or group not supported */
+  CQ_ERR_WORKSPACE = -4,   /* workspace missing, misaligned or too small */
+  CQ_ERR_HIP = -5,         /* a HIP call or kernel launch failed */
+  CQ_ERR_ALIGN = -6        /* a tensor pointer is not 16-byte aligned */
+} cq_status;
+
+/* Which elements share one (min, max) pair - the "statistical range" of Sec. 3.1. */
+enum {
+  CQ_AXIS_CHANNEL = 0, /* one pair per channel over `group` consecutive tokens
+                          (the paper's channel-wise scheme; group = n_vis is the
+                          paper's whole-sequence alpha_i, beta_i) */
+  CQ_AXIS_TOKEN = 1    /* one pair per token over `group` consecutive channels
+                          (the token-wise scheme the paper attributes to KIVI) */
+};
+
+/* Problem shape and quantization scheme shared by both calls. */
+typedef struct {
+  int32_t batch;      /* B  >= 1 */
+  int32_t n_q_heads;  /* Hq, a multiple of n_kv_heads (cq_quantize_kv ignores it) */
+  int32_t n_kv_heads; /* Hkv >= 1 */
+  int32_t head_dim;   /* d: multiple of 32 in [32, 256]; 128 is the tuned case */
+  int32_t n_vis;      /* quantized (visual) tokens per sequence, >= 0 */
+  int32_t bits;       /* b in {1, 2, 4, 8}; 1 and 2 are the tuned cases */
+  int32_t k_axis;     /* CQ_AXIS_* for keys   (hot path: CHANNEL) */
+  int32_t v_axis;     /* CQ_AXIS_* for values (hot path: TOKEN) */
+  int32_t k_group;    /* CHANNEL axis: tokens per group, divides n_vis;
+                         TOKEN axis: channels per group, multiple of 32 dividing d */
+  int32_t v_group;    /* same rule, for values */
+} cq_layout_t;
+
+/*
+ * One quantized tensor of logical shape [B, Hkv, n_vis, d].
+ *   codes  uint32 [B, Hkv, n_vis, d*bits/32].  b-bit codes packed along d; element i
+ *          of a word sits at bits [32-b(1+i), 32-b*i) (appendix pack(v, N=b, M=32)).
+ *   scale  float32, (max-min)/(2^b-1) rounded once to float32.
+ *   min    IEEE fp16 bits of the group minimum (a zero is stored as +0).
+ *          Shape of scale and min: CHANNEL axis [B, Hkv, n_vis/group, d];
+ *                                  TOKEN axis   [B, Hkv, n_vis, d/group].
+ * Dequantized element = code * scale + min (Sec. 2.2 dequantize equation).
+ */
+typedef struct {
+  uint32_t *codes;
+  float *scale;
+  uint16_t *min;
+} cq_qtensor_t;
+
+/*
+ * Quantize the visual KV cache (Sec. 2.2 + Sec. 3.1 + packing appendix).
+ *   k_f16, v_f16  in : fp16 [B, Hkv, n_vis, d]
+ *   k_out, v_out  out: buffers of the shapes above, fully overwritten
+ * code = round((x - min) * (2^b-1) / (max - min)) evaluated exactly with ties to
+ * even; a constant group gives codes 0 and scale 0.  Either of (k_f16, k_out) or
+ * (v_f16, v_out) may be NULL as a pair to quantize only the other tensor.
+ * n_vis == 0 is a successful no-op.
+ */
+int cq_quantize_kv(const cq_layout_t *layout, const void *k_f16, const void *v_f16,
+                   const cq_qtensor_t *k_out, const cq_qtensor_t *v_out, void *stream);
+
+/* Calibration of the visual logits (Sec. 3.2):
+ *   g(x) = (delta-gamma+tau1-tau2)/(delta-gamma) * (x-gamma) + gamma - tau1. */
+enum {
+  CQ_CALIB_NONE = 0,    /* g = identity */
+  CQ_CALIB_DYNAMIC = 1, /* gamma, delta = min, max of the visual logits of each
+                           (batch, query head) row of this call */
+  CQ_CALIB_FIXED = 2    /* gamma, delta taken from this struct */
+};
+typedef struct {
+  int32_t mode;
+  float tau1, tau2;   /* the paper searches {0,1,2,3}; any finite value is accepted */
+  float gamma, delta; /* CQ_CALIB_FIXED only; delta > gamma */
+} cq_calib_t;
+
+/* Bytes of scratch cq_decode_attn needs for this shape (a multiple of 256, > 0).
+ * Returns 0 if the layout is invalid. */
+size_t cq_decode_workspace_bytes(const cq_layout_t *layout, int32_t n_text);
+
+/*
+ * One decode step: out = softmax([g(s_vis), s_txt]) [V_deq; V_text]   (Sec. 2.1, 3.2)
+ *   s_vis[j] = softmax_scale * q . K_deq[j]  over the n_vis quantized tokens,
+ *              computed from the packed codes by post-scaling (Sec. 3.1),
+ *   s_txt[t] = softmax_scale * q . K_text[t] over the first n_text text tokens.
+ *   q_f16        in : fp16 [B, Hq, d]
+ *   k, v         in : quantized visual cache as written by cq_quantize_kv
+ *   k_text_f16,
+ *   v_text_f16   in : fp16 [B, Hkv, n_text_cap, d]; only the first n_text tokens of
+ *                     each head are read; may be NULL when n_text == 0
+ *   calib        in : may be NULL (= CQ_CALIB_NONE)
+ *   softmax_scale   : 0 means 1/sqrt(d)
+ *   out_f16      out: fp16 [B, Hq, d]
+ *   workspace       : device scratch of at least cq_decode_workspace_bytes(), 256-byte
+ *                     aligned; contents undefined before and after; two calls that
+ *                     overlap in time must not share it
+ * n_vis + n_text must be >= 1.
+ */
+int cq_decode_attn(const cq_layout_t *layout, const void *q_f16, const cq_qtensor_t *k,
+                   const cq_qtensor_t *v, const void *k_text_f16, const void *v_text_f16,
+                   int32_t n_text, int32_t n_text_cap, const cq_calib_t *calib,
+                   float softmax_scale, void *out_f16, void *workspace,
+                   size_t workspace_bytes, void *stream);
+
+/* Kernel selection, for tests and comparisons.  AUTO picks the tuned kernels when the
+ * shape allows and the generic ones otherwise; GENERIC forces the shape-agnostic
+ * kernels; TUNED returns CQ_ERR_UNSUPPORTED instead of falling back.  Process-wide.
+ * Returns the previous value, or CQ_ERR_UNSUPPORTED for an unknown one. */
+enum { CQ_PATH_AUTO = 0, CQ_PATH_GENERIC = 1, CQ_PATH_TUNED = 2 };
+int cq_set_kernel_path(int path);
+
+/* Text for a cq_status value; never NULL. */
+const char *cq_status_string(int status);
+/* Message of the last failure on this thread ("" if none). */
+const char *cq_last_error(void);
+/* ABI version: major*10000 + minor*100 + patch. */
+int cq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CQ_H_ */

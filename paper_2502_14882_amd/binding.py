@@ -1,0 +1,191 @@
+"""ctypes binding of libcq.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; this module allocates output
+tensors with torch (device memory and the current stream are all torch is used for)
+and passes raw pointers.  There is no fallback: if libcq.so is missing or a call fails,
+an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcq.so")
+
+CQ_AXIS_CHANNEL, CQ_AXIS_TOKEN = 0, 1
+CQ_CALIB_NONE, CQ_CALIB_DYNAMIC, CQ_CALIB_FIXED = 0, 1, 2
+CQ_PATH_AUTO, CQ_PATH_GENERIC, CQ_PATH_TUNED = 0, 1, 2
+CQ_OK, CQ_ERR_NULL, CQ_ERR_SHAPE, CQ_ERR_UNSUPPORTED = 0, -1, -2, -3
+CQ_ERR_WORKSPACE, CQ_ERR_HIP, CQ_ERR_ALIGN = -4, -5, -6
+
+
+class CqLayout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "batch", "n_q_heads", "n_kv_heads", "head_dim", "n_vis", "bits",
+        "k_axis", "v_axis", "k_group", "v_group")]
+
+
+class CqQTensor(ctypes.Structure):
+    _fields_ = [("codes", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("min", ctypes.c_void_p)]
+
+
+class CqCalib(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int32), ("tau1", ctypes.c_float), ("tau2", ctypes.c_float),
+                ("gamma", ctypes.c_float), ("delta", ctypes.c_float)]
+
+
+class CqError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("cq status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libcq.so (once).  Raises if it has not been built: there is no other path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libcq.so is not built (%s); run `python -m paper_2502_14882_amd.build`" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        P, I, V = ctypes.POINTER, ctypes.c_int32, ctypes.c_void_p
+        L.cq_quantize_kv.restype = ctypes.c_int
+        L.cq_quantize_kv.argtypes = [P(CqLayout), V, V, P(CqQTensor), P(CqQTensor), V]
+        L.cq_decode_workspace_bytes.restype = ctypes.c_size_t
+        L.cq_decode_workspace_bytes.argtypes = [P(CqLayout), I]
+        L.cq_decode_attn.restype = ctypes.c_int
+        L.cq_decode_attn.argtypes = [P(CqLayout), V, P(CqQTensor), P(CqQTensor), V, V, I, I,
+                                     P(CqCalib), ctypes.c_float, V, V, ctypes.c_size_t, V]
+        L.cq_set_kernel_path.restype = ctypes.c_int
+        L.cq_set_kernel_path.argtypes = [ctypes.c_int]
+        L.cq_status_string.restype = ctypes.c_char_p
+        L.cq_status_string.argtypes = [ctypes.c_int]
+        L.cq_last_error.restype = ctypes.c_char_p
+        L.cq_last_error.argtypes = []
+        L.cq_version.restype = ctypes.c_int
+        L.cq_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != CQ_OK:
+        L = lib()
+        msg = L.cq_last_error().decode() or L.cq_status_string(status).decode()
+        raise CqError(status, msg)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(t: torch.Tensor) -> Optional[int]:
+    if t.is_cuda:
+        return torch.cuda.current_stream(t.device).cuda_stream or None
+    return None
+
+
+class QTensor(NamedTuple):
+    """Device buffers of one quantized [B, Hkv, n_vis, d] tensor."""
+    codes: torch.Tensor   # int32 storage of the uint32 words [B, Hkv, n_vis, d*bits/32]
+    scale: torch.Tensor   # float32
+    min: torch.Tensor     # float16
+
+    def c_struct(self) -> CqQTensor:
+        return CqQTensor(self.codes.data_ptr(), self.scale.data_ptr(), self.min.data_ptr())
+
+
+def make_layout(batch, n_q_heads, n_kv_heads, head_dim, n_vis, bits=1,
+                k_axis=CQ_AXIS_CHANNEL, v_axis=CQ_AXIS_TOKEN, k_group=128, v_group=128) -> CqLayout:
+    return CqLayout(batch, n_q_heads, n_kv_heads, head_dim, n_vis, bits, k_axis, v_axis,
+                    k_group, v_group)
+
+
+def _meta_shape(layout: CqLayout, axis: int, group: int):
+    B, H, n, d = layout.batch, layout.n_kv_heads, layout.n_vis, layout.head_dim
+    if axis == CQ_AXIS_CHANNEL:
+        return (B, H, n // max(group, 1), d)
+    return (B, H, n, d // max(group, 1))
+
+
+def alloc_qtensor(layout: CqLayout, axis: int, group: int, device) -> QTensor:
+    B, H, n, d = layout.batch, layout.n_kv_heads, layout.n_vis, layout.head_dim
+    codes = torch.empty((B, H, n, d * layout.bits // 32), dtype=torch.int32, device=device)
+    shape = _meta_shape(layout, axis, group)
+    return QTensor(codes, torch.empty(shape, dtype=torch.float32, device=device),
+                   torch.empty(shape, dtype=torch.float16, device=device))
+
+
+def cq_quantize_kv(layout: CqLayout, k: Optional[torch.Tensor], v: Optional[torch.Tensor],
+                   k_out: Optional[QTensor] = None, v_out: Optional[QTensor] = None):
+    """Quantize fp16 k, v [B, Hkv, n_vis, d]; returns (k_out, v_out) QTensors."""
+    ref = k if k is not None else v
+    if k is not None and k_out is None:
+        k_out = alloc_qtensor(layout, layout.k_axis, layout.k_group, k.device)
+    if v is not None and v_out is None:
+        v_out = alloc_qtensor(layout, layout.v_axis, layout.v_group, v.device)
+    for t in (k, v):
+        if t is not None:
+            assert t.dtype == torch.float16 and t.is_contiguous()
+    ks = k_out.c_struct() if k_out is not None else None
+    vs = v_out.c_struct() if v_out is not None else None
+    _check(lib().cq_quantize_kv(ctypes.byref(layout), _ptr(k), _ptr(v),
+                                ctypes.byref(ks) if ks is not None else None,
+                                ctypes.byref(vs) if vs is not None else None,
+                                _stream(ref) if ref is not None else None))
+    return k_out, v_out
+
+
+def cq_decode_workspace_bytes(layout: CqLayout, n_text: int) -> int:
+    return int(lib().cq_decode_workspace_bytes(ctypes.byref(layout), int(n_text)))
+
+
+def make_calib(mode=CQ_CALIB_NONE, tau1=0.0, tau2=0.0, gamma=0.0, delta=0.0) -> CqCalib:
+    return CqCalib(mode, tau1, tau2, gamma, delta)
+
+
+def cq_decode_attn(layout: CqLayout, q: torch.Tensor, k: Optional[QTensor], v: Optional[QTensor],
+                   k_text: Optional[torch.Tensor], v_text: Optional[torch.Tensor],
+                   n_text: int, calib: Optional[CqCalib] = None, softmax_scale: float = 0.0,
+                   out: Optional[torch.Tensor] = None,
+                   workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One decode step; returns out [B, Hq, d] fp16 (allocated here unless given)."""
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        workspace = torch.empty(cq_decode_workspace_bytes(layout, n_text), dtype=torch.uint8,
+                                device=q.device)
+    n_text_cap = 0
+    if k_text is not None:
+        assert k_text.dtype == torch.float16 and k_text.is_contiguous()
+        assert v_text is not None and v_text.shape == k_text.shape and v_text.is_contiguous()
+        n_text_cap = k_text.shape[2]
+    ks = k.c_struct() if k is not None else None
+    vs = v.c_struct() if v is not None else None
+    _check(lib().cq_decode_attn(
+        ctypes.byref(layout), _ptr(q),
+        ctypes.byref(ks) if ks is not None else None,
+        ctypes.byref(vs) if vs is not None else None,
+        _ptr(k_text), _ptr(v_text), int(n_text), int(n_text_cap),
+        ctypes.byref(calib) if calib is not None else None, float(softmax_scale),
+        _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(q)))
+    return out
+
+
+def cq_set_kernel_path(path: int) -> int:
+    r = lib().cq_set_kernel_path(int(path))
+    if r < 0:
+        _check(r)
+    return r
+
+
+def cq_version() -> int:
+    return int(lib().cq_version())

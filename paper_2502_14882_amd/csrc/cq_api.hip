@@ -1,0 +1,223 @@
+// Host side of libcq: argument validation, kernel-path selection, status strings.
+// Every check here runs before the first HIP call, so a rejected call launches nothing.
+#include <atomic>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "cq_internal.h"
+
+namespace {
+
+thread_local char g_last_error[256] = "";
+std::atomic<int> g_kernel_path{CQ_PATH_AUTO};
+
+int fail(int status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_last_error, sizeof(g_last_error), fmt, ap);
+  va_end(ap);
+  return status;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_group(const char* which, int axis, int group, int n_vis, int d) {
+  if (axis == CQ_AXIS_CHANNEL) {
+    if (group < 1) return fail(CQ_ERR_SHAPE, "%s_group must be >= 1 (got %d)", which, group);
+    if (n_vis % group != 0)
+      return fail(CQ_ERR_SHAPE, "n_vis=%d is not a multiple of %s_group=%d", n_vis, which, group);
+  } else if (axis == CQ_AXIS_TOKEN) {
+    if (group < 32 || group % 32 != 0 || d % group != 0)
+      return fail(CQ_ERR_SHAPE,
+                  "%s_group=%d must be a multiple of 32 that divides head_dim=%d", which, group, d);
+  } else {
+    return fail(CQ_ERR_UNSUPPORTED, "%s_axis=%d is not a CQ_AXIS_* value", which, axis);
+  }
+  return CQ_OK;
+}
+
+int check_layout(const cq_layout_t* L, bool need_q_heads) {
+  if (!L) return fail(CQ_ERR_NULL, "layout is NULL");
+  if (L->batch < 1 || L->n_kv_heads < 1)
+    return fail(CQ_ERR_SHAPE, "batch=%d and n_kv_heads=%d must be >= 1", L->batch, L->n_kv_heads);
+  if (need_q_heads && (L->n_q_heads < 1 || L->n_q_heads % L->n_kv_heads != 0))
+    return fail(CQ_ERR_SHAPE, "n_q_heads=%d must be a positive multiple of n_kv_heads=%d",
+                L->n_q_heads, L->n_kv_heads);
+  if (L->head_dim < 32 || L->head_dim > 256 || L->head_dim % 32 != 0)
+    return fail(CQ_ERR_SHAPE, "head_dim=%d must be a multiple of 32 in [32, 256]", L->head_dim);
+  if (L->n_vis < 0) return fail(CQ_ERR_SHAPE, "n_vis=%d must be >= 0", L->n_vis);
+  if (L->bits != 1 && L->bits != 2 && L->bits != 4 && L->bits != 8)
+    return fail(CQ_ERR_UNSUPPORTED, "bits=%d not in {1, 2, 4, 8}", L->bits);
+  int rc = check_group("k", L->k_axis, L->k_group, L->n_vis, L->head_dim);
+  if (rc != CQ_OK) return rc;
+  rc = check_group("v", L->v_axis, L->v_group, L->n_vis, L->head_dim);
+  if (rc != CQ_OK) return rc;
+  const double elems = (double)L->batch * L->n_kv_heads * (double)L->n_vis * L->head_dim;
+  if (elems >= 9.0e18) return fail(CQ_ERR_SHAPE, "tensor too large");
+  return CQ_OK;
+}
+
+int check_qtensor(const char* which, const cq_qtensor_t* t) {
+  if (!t) return fail(CQ_ERR_NULL, "%s is NULL", which);
+  if (!t->codes || !t->scale || !t->min)
+    return fail(CQ_ERR_NULL, "%s has a NULL codes/scale/min pointer", which);
+  if (!aligned16(t->codes) || !aligned16(t->scale) || !aligned16(t->min))
+    return fail(CQ_ERR_ALIGN, "%s buffers must be 16-byte aligned", which);
+  return CQ_OK;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  return fail(CQ_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+int cq_version(void) { return 100; }
+
+const char* cq_last_error(void) { return g_last_error; }
+
+const char* cq_status_string(int status) {
+  switch (status) {
+    case CQ_OK: return "CQ_OK";
+    case CQ_ERR_NULL: return "CQ_ERR_NULL: a required pointer is NULL";
+    case CQ_ERR_SHAPE: return "CQ_ERR_SHAPE: sizes out of range or not divisible";
+    case CQ_ERR_UNSUPPORTED: return "CQ_ERR_UNSUPPORTED: bits, axis or group not supported";
+    case CQ_ERR_WORKSPACE: return "CQ_ERR_WORKSPACE: workspace missing, misaligned or too small";
+    case CQ_ERR_HIP: return "CQ_ERR_HIP: a HIP call or kernel launch failed";
+    case CQ_ERR_ALIGN: return "CQ_ERR_ALIGN: a tensor pointer is not 16-byte aligned";
+    default: return "unknown cq_status";
+  }
+}
+
+int cq_set_kernel_path(int path) {
+  if (path != CQ_PATH_AUTO && path != CQ_PATH_GENERIC && path != CQ_PATH_TUNED)
+    return fail(CQ_ERR_UNSUPPORTED, "unknown kernel path %d", path);
+  return g_kernel_path.exchange(path);
+}
+
+size_t cq_decode_workspace_bytes(const cq_layout_t* L, int32_t n_text) {
+  if (check_layout(L, true) != CQ_OK || n_text < 0) return 0;
+  return cq::workspace_layout(L->batch, L->n_q_heads, L->head_dim, L->n_vis, n_text).total_bytes;
+}
+
+int cq_quantize_kv(const cq_layout_t* L, const void* k_f16, const void* v_f16,
+                   const cq_qtensor_t* k_out, const cq_qtensor_t* v_out, void* stream) {
+  int rc = check_layout(L, false);
+  if (rc != CQ_OK) return rc;
+  const bool do_k = (k_f16 != nullptr) || (k_out != nullptr);
+  const bool do_v = (v_f16 != nullptr) || (v_out != nullptr);
+  if (!do_k && !do_v) return fail(CQ_ERR_NULL, "both the key and the value pair are NULL");
+  if (do_k) {
+    if (!k_f16) return fail(CQ_ERR_NULL, "k_f16 is NULL but k_out is not");
+    if ((rc = check_qtensor("k_out", k_out)) != CQ_OK) return rc;
+    if (!aligned16(k_f16)) return fail(CQ_ERR_ALIGN, "k_f16 must be 16-byte aligned");
+  }
+  if (do_v) {
+    if (!v_f16) return fail(CQ_ERR_NULL, "v_f16 is NULL but v_out is not");
+    if ((rc = check_qtensor("v_out", v_out)) != CQ_OK) return rc;
+    if (!aligned16(v_f16)) return fail(CQ_ERR_ALIGN, "v_f16 must be 16-byte aligned");
+  }
+  if (L->n_vis == 0) return CQ_OK;
+  const int path = g_kernel_path.load();
+  if (path == CQ_PATH_TUNED)
+    return fail(CQ_ERR_UNSUPPORTED, "no tuned quantizer for this layout");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int rows = L->batch * L->n_kv_heads;
+  if (do_k) {
+    hipError_t e = cq::launch_quantize_generic(k_f16, *k_out, rows, L->n_vis, L->head_dim, L->bits,
+                                               L->k_axis, L->k_group, s);
+    if (e != hipSuccess) return hip_fail(e, "quantize keys");
+  }
+  if (do_v) {
+    hipError_t e = cq::launch_quantize_generic(v_f16, *v_out, rows, L->n_vis, L->head_dim, L->bits,
+                                               L->v_axis, L->v_group, s);
+    if (e != hipSuccess) return hip_fail(e, "quantize values");
+  }
+  return CQ_OK;
+}
+
+int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* k,
+                   const cq_qtensor_t* v, const void* k_text_f16, const void* v_text_f16,
+                   int32_t n_text, int32_t n_text_cap, const cq_calib_t* calib,
+                   float softmax_scale, void* out_f16, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+  int rc = check_layout(L, true);
+  if (rc != CQ_OK) return rc;
+  if (!q_f16 || !out_f16) return fail(CQ_ERR_NULL, "q_f16 or out_f16 is NULL");
+  if (!aligned16(q_f16) || !aligned16(out_f16))
+    return fail(CQ_ERR_ALIGN, "q_f16 and out_f16 must be 16-byte aligned");
+  if (n_text < 0 || n_text_cap < n_text)
+    return fail(CQ_ERR_SHAPE, "need 0 <= n_text (%d) <= n_text_cap (%d)", n_text, n_text_cap);
+  if ((long long)L->n_vis + n_text < 1)
+    return fail(CQ_ERR_SHAPE, "nothing to attend to: n_vis + n_text == 0");
+  if (L->n_vis > 0) {
+    if ((rc = check_qtensor("k", k)) != CQ_OK) return rc;
+    if ((rc = check_qtensor("v", v)) != CQ_OK) return rc;
+  }
+  if (n_text > 0) {
+    if (!k_text_f16 || !v_text_f16)
+      return fail(CQ_ERR_NULL, "n_text=%d but k_text_f16 or v_text_f16 is NULL", n_text);
+    if (!aligned16(k_text_f16) || !aligned16(v_text_f16))
+      return fail(CQ_ERR_ALIGN, "text-tail tensors must be 16-byte aligned");
+  }
+  cq::Calib c{CQ_CALIB_NONE, 0.f, 0.f, 0.f, 0.f};
+  if (calib) {
+    if (calib->mode != CQ_CALIB_NONE && calib->mode != CQ_CALIB_DYNAMIC &&
+        calib->mode != CQ_CALIB_FIXED)
+      return fail(CQ_ERR_UNSUPPORTED, "calib mode %d is not a CQ_CALIB_* value", calib->mode);
+    c.mode = calib->mode;
+    if (c.mode != CQ_CALIB_NONE) {
+      if (!std::isfinite(calib->tau1) || !std::isfinite(calib->tau2))
+        return fail(CQ_ERR_SHAPE, "tau1 and tau2 must be finite");
+      c.tau1 = calib->tau1;
+      c.tau2 = calib->tau2;
+    }
+    if (c.mode == CQ_CALIB_FIXED) {
+      if (!std::isfinite(calib->gamma) || !std::isfinite(calib->delta) ||
+          !(calib->delta > calib->gamma))
+        return fail(CQ_ERR_SHAPE, "CQ_CALIB_FIXED needs finite delta > gamma");
+      c.gamma = calib->gamma;
+      c.delta = calib->delta;
+    }
+  }
+  if (!std::isfinite(softmax_scale) || softmax_scale < 0.f)
+    return fail(CQ_ERR_SHAPE, "softmax_scale must be finite and >= 0");
+  if (softmax_scale == 0.f) softmax_scale = 1.0f / std::sqrt((float)L->head_dim);
+
+  const cq::Workspace wl =
+      cq::workspace_layout(L->batch, L->n_q_heads, L->head_dim, L->n_vis, n_text);
+  if (!workspace) return fail(CQ_ERR_WORKSPACE, "workspace is NULL");
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(CQ_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (workspace_bytes < wl.total_bytes)
+    return fail(CQ_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes,
+                wl.total_bytes);
+
+  const int path = g_kernel_path.load();
+  if (path == CQ_PATH_TUNED)
+    return fail(CQ_ERR_UNSUPPORTED, "no tuned decode kernel for this layout");
+
+  cq::DecodeShape s;
+  s.B = L->batch; s.Hq = L->n_q_heads; s.Hkv = L->n_kv_heads; s.g = s.Hq / s.Hkv;
+  s.d = L->head_dim; s.n_vis = L->n_vis; s.n_text = n_text; s.n_text_cap = n_text_cap;
+  s.bits = L->bits; s.k_axis = L->k_axis; s.v_axis = L->v_axis;
+  s.k_group = L->k_group; s.v_group = L->v_group;
+  s.n_vis_chunks = cq::ceil_div(s.n_vis, cq::kVisChunk);
+  s.n_text_chunks = cq::ceil_div(s.n_text, cq::kTextChunk);
+  s.n_chunks = s.n_vis_chunks + s.n_text_chunks;
+  s.words_per_token = s.d * s.bits / 32;
+
+  static const cq_qtensor_t kNone = {nullptr, nullptr, nullptr};
+  hipError_t e = cq::launch_decode_generic(s, q_f16, k ? *k : kNone, v ? *v : kNone, k_text_f16,
+                                           v_text_f16, c, softmax_scale, out_f16,
+                                           static_cast<float*>(workspace), wl,
+                                           static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "decode attention");
+  return CQ_OK;
+}
+
+}  // extern "C"

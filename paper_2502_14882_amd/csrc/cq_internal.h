@@ -1,0 +1,67 @@
+// Internal declarations shared by the host API and the HIP kernels of libcq.
+// Not part of the ABI (see include/cq.h for that).
+#ifndef CQ_INTERNAL_H_
+#define CQ_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "cq.h"
+
+namespace cq {
+
+// Tokens per block-level work item of the decode pipeline.  A "chunk" is the unit of
+// split-K: every chunk produces one (m, l, acc[d]) partial of the online softmax.
+constexpr int kVisChunk = 512;
+constexpr int kTextChunk = 512;
+
+struct DecodeShape {
+  int B, Hq, Hkv, g, d, n_vis, n_text, n_text_cap;
+  int bits, k_axis, v_axis, k_group, v_group;
+  int n_vis_chunks, n_text_chunks, n_chunks;
+  int words_per_token;  // d * bits / 32
+};
+
+// Layout of the caller-provided workspace (all float, offsets in floats).
+struct Workspace {
+  size_t logits;    // [B][Hq][n_vis + n_text]       raw (uncalibrated) logits
+  size_t minmax;    // [B][Hq][n_chunks][2]          min, max of each chunk's logits
+  size_t partial;   // [B][Hq][n_chunks][d + 2]      m, l, acc[d]
+  size_t total_bytes;
+};
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+inline Workspace workspace_layout(int B, int Hq, int d, int n_vis, int n_text) {
+  Workspace w;
+  const int nvc = ceil_div(n_vis, kVisChunk), ntc = ceil_div(n_text, kTextChunk);
+  const size_t rows = (size_t)B * (size_t)Hq;
+  auto align64 = [](size_t x) { return (x + 63) / 64 * 64; };
+  w.logits = 0;
+  w.minmax = align64(w.logits + rows * ((size_t)n_vis + (size_t)n_text));
+  w.partial = align64(w.minmax + rows * (size_t)(nvc + ntc) * 2);
+  size_t end = align64(w.partial + rows * (size_t)(nvc + ntc) * (size_t)(d + 2));
+  w.total_bytes = (end * sizeof(float) + 255) / 256 * 256;
+  if (w.total_bytes == 0) w.total_bytes = 256;
+  return w;
+}
+
+struct Calib {
+  int mode;
+  float tau1, tau2, gamma, delta;
+};
+
+// ---- launchers (each returns the hipError_t of its launches) -----------------------
+hipError_t launch_quantize_generic(const void* x_f16, const cq_qtensor_t& out, int rows,
+                                   int n_vis, int d, int bits, int axis, int group,
+                                   hipStream_t stream);
+
+hipError_t launch_decode_generic(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
+                                 const cq_qtensor_t& v, const void* k_text, const void* v_text,
+                                 const Calib& calib, float softmax_scale, void* out,
+                                 float* workspace, const Workspace& wl, hipStream_t stream);
+
+}  // namespace cq
+
+#endif  // CQ_INTERNAL_H_

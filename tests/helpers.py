@@ -1,0 +1,57 @@
+"""Shared plumbing of the GPU parity tests: run the oracle and the HIP path on the same tensors."""
+import numpy as np
+import torch
+
+from oracle import cq_oracle as O
+from paper_2502_14882_amd import binding as cq
+from paper_2502_14882_amd import synth
+
+REL_L2_TOL = 2e-3      # fp16 output, fp32 accumulation, against the fp64 oracle
+
+
+def layout_of(w: synth.Workload, bits=1, k_group=128, v_group=128, k_axis=0, v_axis=1):
+    return cq.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_vis, bits,
+                          k_axis, v_axis, k_group, v_group)
+
+
+def oracle_quantize(x_cpu: dict, lay):
+    kq = O.quantize_tensor(x_cpu["k"].numpy(), lay.bits, lay.k_axis, lay.k_group)
+    vq = O.quantize_tensor(x_cpu["v"].numpy(), lay.bits, lay.v_axis, lay.v_group)
+    return kq, vq
+
+
+def words_of(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)
+
+
+def assert_qtensor_equal(gpu, ref, what=""):
+    """Bit-exact comparison of packed words, scale bits and min bits."""
+    w = words_of(gpu.codes)
+    assert w.shape == ref["words"].shape, (what, w.shape, ref["words"].shape)
+    bad = np.count_nonzero(w != ref["words"])
+    assert bad == 0, "%s: %d of %d code words differ" % (what, bad, w.size)
+    s = gpu.scale.cpu().numpy().view(np.uint32)
+    bad = np.count_nonzero(s != ref["scale"].view(np.uint32))
+    assert bad == 0, "%s: %d of %d scales differ in bits" % (what, bad, s.size)
+    m = gpu.min.cpu().numpy().view(np.uint16)
+    bad = np.count_nonzero(m != ref["min"].view(np.uint16))
+    assert bad == 0, "%s: %d of %d mins differ in bits" % (what, bad, m.size)
+
+
+def to_device(x_cpu: dict, device="cuda"):
+    return {k: v.to(device) for k, v in x_cpu.items()}
+
+
+def oracle_decode(x_cpu, kq, vq, n_text, mode, tau1=0.0, tau2=0.0, gamma=0.0, delta=0.0,
+                  softmax_scale=0.0):
+    kt = x_cpu["k_text"].numpy() if n_text > 0 else None
+    vt = x_cpu["v_text"].numpy() if n_text > 0 else None
+    return O.decode_attn(x_cpu["q"].numpy(), kq, vq, kt, vt, n_text, mode, tau1, tau2, gamma,
+                         delta, softmax_scale)
+
+
+def row_rel_l2(out, ref):
+    out = np.asarray(out, np.float64)
+    num = np.linalg.norm(out - ref, axis=-1)
+    den = np.linalg.norm(ref, axis=-1)
+    return float((num / np.where(den > 0, den, 1.0)).max())

@@ -1,0 +1,115 @@
+"""C-ABI checks that need no GPU: the library loads, exports what include/cq.h declares, and
+rejects bad arguments on the host before any HIP call (fake non-NULL pointers are never
+dereferenced because no launch happens)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_14882_amd import binding as cq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000     # aligned, non-NULL, never touched
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "cq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert {"cq_quantize_kv", "cq_decode_attn", "cq_decode_workspace_bytes", "cq_status_string",
+            "cq_last_error", "cq_version", "cq_set_kernel_path"} <= set(names)
+    L = cq.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert cq.cq_version() >= 100
+
+
+def test_struct_sizes_match_header():
+    assert ctypes.sizeof(cq.CqLayout) == 40
+    assert ctypes.sizeof(cq.CqQTensor) == 3 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(cq.CqCalib) == 20
+
+
+def _quant(layout, k=FAKE, v=FAKE, ko=(FAKE, FAKE, FAKE), vo=(FAKE, FAKE, FAKE)):
+    ks = cq.CqQTensor(*ko) if ko is not None else None
+    vs = cq.CqQTensor(*vo) if vo is not None else None
+    return cq.lib().cq_quantize_kv(ctypes.byref(layout), k, v,
+                                   ctypes.byref(ks) if ks else None,
+                                   ctypes.byref(vs) if vs else None, None)
+
+
+def test_quantize_argument_errors():
+    ok = dict(batch=1, n_q_heads=4, n_kv_heads=2, head_dim=128, n_vis=256)
+    assert _quant(cq.make_layout(**{**ok, "n_vis": 0})) == cq.CQ_OK          # empty: no-op
+    assert _quant(cq.make_layout(**ok), k=None) == cq.CQ_ERR_NULL
+    assert _quant(cq.make_layout(**ok), ko=(FAKE, None, FAKE)) == cq.CQ_ERR_NULL
+    assert _quant(cq.make_layout(**ok), k=None, ko=None, v=None, vo=None) == cq.CQ_ERR_NULL
+    assert _quant(cq.make_layout(**ok), k=FAKE + 2) == cq.CQ_ERR_ALIGN
+    assert _quant(cq.make_layout(**{**ok, "head_dim": 100})) == cq.CQ_ERR_SHAPE
+    assert _quant(cq.make_layout(**{**ok, "head_dim": 512})) == cq.CQ_ERR_SHAPE
+    assert _quant(cq.make_layout(**ok, bits=3)) == cq.CQ_ERR_UNSUPPORTED
+    assert _quant(cq.make_layout(**ok, k_group=96)) == cq.CQ_ERR_SHAPE         # 256 % 96
+    assert _quant(cq.make_layout(**ok, v_group=48)) == cq.CQ_ERR_SHAPE         # not mult of 32
+    assert _quant(cq.make_layout(**ok, k_axis=7)) == cq.CQ_ERR_UNSUPPORTED
+    assert _quant(cq.make_layout(**{**ok, "batch": 0})) == cq.CQ_ERR_SHAPE
+    _quant(cq.make_layout(**ok, k_group=96))
+    assert b"k_group" in cq.lib().cq_last_error()
+
+
+def _decode(layout, n_text=4, cap=4, calib=None, ws=FAKE, ws_bytes=1 << 40, q=FAKE, out=FAKE,
+            kt=FAKE, vt=FAKE, scale=0.0, k=(FAKE, FAKE, FAKE)):
+    ks, vs = cq.CqQTensor(*k), cq.CqQTensor(FAKE, FAKE, FAKE)
+    return cq.lib().cq_decode_attn(ctypes.byref(layout), q, ctypes.byref(ks), ctypes.byref(vs),
+                                   kt, vt, n_text, cap,
+                                   ctypes.byref(calib) if calib is not None else None, scale, out,
+                                   ws, ws_bytes, None)
+
+
+def test_decode_argument_errors():
+    lay = cq.make_layout(2, 8, 2, 128, 256)
+    assert _decode(lay, q=None) == cq.CQ_ERR_NULL
+    assert _decode(lay, kt=None) == cq.CQ_ERR_NULL
+    assert _decode(lay, k=(None, FAKE, FAKE)) == cq.CQ_ERR_NULL
+    assert _decode(lay, n_text=5, cap=4) == cq.CQ_ERR_SHAPE
+    assert _decode(lay, n_text=-1) == cq.CQ_ERR_SHAPE
+    assert _decode(lay, ws=None) == cq.CQ_ERR_WORKSPACE
+    assert _decode(lay, ws=FAKE + 16) == cq.CQ_ERR_WORKSPACE
+    assert _decode(lay, ws_bytes=1024) == cq.CQ_ERR_WORKSPACE
+    assert _decode(lay, out=FAKE + 8) == cq.CQ_ERR_ALIGN
+    assert _decode(lay, calib=cq.make_calib(9)) == cq.CQ_ERR_UNSUPPORTED
+    assert _decode(lay, calib=cq.make_calib(cq.CQ_CALIB_FIXED, 1, 2, 3.0, 3.0)) == cq.CQ_ERR_SHAPE
+    assert _decode(lay, calib=cq.make_calib(cq.CQ_CALIB_DYNAMIC, float("nan"), 0)) == cq.CQ_ERR_SHAPE
+    assert _decode(lay, scale=-1.0) == cq.CQ_ERR_SHAPE
+    assert _decode(cq.make_layout(2, 7, 2, 128, 256)) == cq.CQ_ERR_SHAPE       # Hq % Hkv
+    assert _decode(cq.make_layout(1, 1, 1, 128, 0), n_text=0, cap=0) == cq.CQ_ERR_SHAPE
+    assert cq.lib().cq_status_string(cq.CQ_ERR_WORKSPACE).startswith(b"CQ_ERR_WORKSPACE")
+
+
+def test_workspace_size_rule():
+    lay = cq.make_layout(2, 8, 2, 128, 1024)
+    n = cq.cq_decode_workspace_bytes(lay, 32)
+    assert n > 0 and n % 256 == 0
+    # it at least holds one fp32 logit per (batch, query head, token)
+    assert n >= 2 * 8 * (1024 + 32) * 4
+    assert cq.cq_decode_workspace_bytes(cq.make_layout(2, 8, 2, 100, 1024), 32) == 0
+    bigger = cq.cq_decode_workspace_bytes(cq.make_layout(2, 8, 2, 128, 4096), 32)
+    assert bigger > n
+
+
+def test_kernel_path_switch():
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_GENERIC)
+    assert cq.cq_set_kernel_path(prev) == cq.CQ_PATH_GENERIC
+    with pytest.raises(cq.CqError):
+        cq.cq_set_kernel_path(42)
+
+
+def test_binding_raises_when_library_is_missing(monkeypatch):
+    monkeypatch.setattr(cq, "_lib", None)
+    monkeypatch.setattr(cq, "LIB_PATH", "/nonexistent/libcq.so")
+    with pytest.raises(RuntimeError, match="not built"):
+        cq.lib()

@@ -1,0 +1,145 @@
+"""GPU parity of cq_decode_attn against the fp64 oracle: relative L2 <= 2e-3 on the fp16 output.
+
+The HIP path consumes the cache written by cq_quantize_kv (asserted bit-identical to the
+oracle's), so both sides attend over exactly the same quantized numbers."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cq_oracle as O
+from paper_2502_14882_amd import binding as cq
+from paper_2502_14882_amd import synth
+
+import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+class Case:
+    """Inputs on both sides plus the quantized cache, built once per workload/layout."""
+
+    def __init__(self, w, lay, x_cpu=None):
+        self.w, self.lay = w, lay
+        self.x_cpu = x_cpu or synth.make_inputs(w, "cpu")
+        self.kq, self.vq = H.oracle_quantize(self.x_cpu, lay)
+        self.x = H.to_device(self.x_cpu)
+        if w.n_vis > 0:
+            self.k_dev, self.v_dev = cq.cq_quantize_kv(lay, self.x["k"], self.x["v"])
+            H.assert_qtensor_equal(self.k_dev, self.kq, "keys")
+            H.assert_qtensor_equal(self.v_dev, self.vq, "values")
+        else:
+            self.k_dev = self.v_dev = None
+
+    def check(self, mode=cq.CQ_CALIB_DYNAMIC, tau1=1.0, tau2=2.0, gamma=0.0, delta=0.0,
+              n_text=None, softmax_scale=0.0, tol=H.REL_L2_TOL):
+        n_text = self.w.n_text if n_text is None else n_text
+        ref = H.oracle_decode(self.x_cpu, self.kq, self.vq, n_text, mode, tau1, tau2, gamma, delta,
+                              softmax_scale)
+        kt = self.x["k_text"] if self.x["k_text"].shape[2] > 0 else None
+        vt = self.x["v_text"] if kt is not None else None
+        out = cq.cq_decode_attn(self.lay, self.x["q"], self.k_dev, self.v_dev, kt, vt, n_text,
+                                cq.make_calib(mode, tau1, tau2, gamma, delta), softmax_scale)
+        torch.cuda.synchronize()
+        out = out.cpu().numpy().astype(np.float64)
+        assert np.isfinite(out).all()
+        err, worst = O.rel_l2(out, ref), H.row_rel_l2(out, ref)
+        assert err <= tol, "rel L2 %.3e (worst row %.3e) > %.1e" % (err, worst, tol)
+        assert worst <= 4 * tol, "worst row rel L2 %.3e" % worst
+        return err
+
+
+@pytest.fixture(scope="module")
+def cfg0():
+    w = synth.WORKLOADS[0]
+    return Case(w, H.layout_of(w))
+
+
+@pytest.mark.parametrize("tau1,tau2", list(itertools.product([0, 1, 2, 3], repeat=2)))
+def test_config0_every_tau_pair_of_the_papers_grid(cfg0, tau1, tau2):
+    cfg0.check(cq.CQ_CALIB_DYNAMIC, float(tau1), float(tau2))
+
+
+def test_config0_modes(cfg0):
+    cfg0.check(cq.CQ_CALIB_NONE)
+    cfg0.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-20.0, delta=25.0)
+    cfg0.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, softmax_scale=0.05)
+    cfg0.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, n_text=0)
+    cfg0.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, n_text=17)       # capacity 32, 17 used
+
+
+def test_calibration_with_nonpositive_slope_is_applied_literally(cfg0):
+    # delta - gamma + tau1 - tau2 < 0 flips the order of the visual logits; no clamping
+    cfg0.check(cq.CQ_CALIB_FIXED, 0.0, 30.0, gamma=-1.0, delta=1.0)
+
+
+SHRUNK = {
+    1: dict(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1280, n_text=128),       # g = 4
+    2: dict(batch=3, n_kv_heads=2, n_q_heads=8, n_vis=1536, n_text=600),       # two text chunks
+    4: dict(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=4096, n_text=300),      # g = 6, split-K
+}
+
+
+@pytest.mark.parametrize("idx", [1, 2, 4])
+@pytest.mark.parametrize("bits", [1, 2])
+def test_shrunk_configs(idx, bits):
+    w = synth.WORKLOADS[idx].replace(**SHRUNK[idx])
+    c = Case(w, H.layout_of(w, bits))
+    c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    c.check(cq.CQ_CALIB_NONE)
+
+
+@pytest.mark.parametrize("kg,vg", [(32, 32), (64, 128), (128, 64)])
+def test_group_sizes(kg, vg):
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=640, n_text=40)
+    Case(w, H.layout_of(w, 1, kg, vg)).check()
+
+
+def test_ragged_sizes_and_single_tokens():
+    # n_vis not a multiple of the chunk, text tail of 1, then visual-only and text-only
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=1, n_q_heads=4, n_vis=896, n_text=1)
+    Case(w, H.layout_of(w)).check()
+    w = synth.WORKLOADS[1].replace(batch=1, n_kv_heads=1, n_q_heads=2, n_vis=128, n_text=0)
+    Case(w, H.layout_of(w)).check()
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=4, n_vis=0, n_text=77)
+    Case(w, H.layout_of(w)).check()
+
+
+def test_paper_literal_channelwise_values_and_other_layouts():
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=4, n_vis=512, n_text=33)
+    Case(w, H.layout_of(w, 1, 128, 128, 0, 0)).check()           # channel-wise K and V
+    Case(w, H.layout_of(w, 2, 512, 512, 0, 0)).check()           # whole-sequence statistics
+    Case(w, H.layout_of(w, 2, 64, 64, 1, 1)).check()             # token-wise K and V
+    Case(w, H.layout_of(w, 4, 64, 64)).check()
+    Case(w, H.layout_of(w, 8, 64, 64)).check()
+
+
+@pytest.mark.parametrize("d", [64, 256])
+def test_other_head_dims(d):
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=4, head_dim=d, n_vis=256,
+                                   n_text=20)
+    Case(w, H.layout_of(w, 1, 64, 32)).check()
+
+
+def test_many_query_heads_per_kv_head():
+    w = synth.WORKLOADS[1].replace(batch=1, n_kv_heads=1, n_q_heads=11, n_vis=256, n_text=9)
+    Case(w, H.layout_of(w)).check()
+
+
+def test_constant_visual_logits_give_slope_one():
+    # all keys identical -> every visual logit equal -> delta == gamma
+    w = synth.WORKLOADS[0].replace(n_vis=256, n_text=8)
+    x = synth.make_inputs(w, "cpu")
+    x["k"][:] = x["k"][:, :, :1, :]
+    Case(w, H.layout_of(w), x).check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+
+
+def test_output_is_deterministic(cfg0):
+    outs = []
+    for _ in range(2):
+        o = cq.cq_decode_attn(cfg0.lay, cfg0.x["q"], cfg0.k_dev, cfg0.v_dev, cfg0.x["k_text"],
+                              cfg0.x["v_text"], 32, cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1, 2))
+        torch.cuda.synchronize()
+        outs.append(o.cpu())
+    assert torch.equal(outs[0], outs[1])

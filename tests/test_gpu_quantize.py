@@ -1,0 +1,109 @@
+"""GPU parity of cq_quantize_kv against the oracle: packed codes, scale and min bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_14882_amd import binding as cq
+from paper_2502_14882_amd import synth
+
+import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(w, lay, x_cpu=None, what=""):
+    x_cpu = x_cpu or synth.make_inputs(w, "cpu", parts=("k", "v"))
+    kq, vq = H.oracle_quantize(x_cpu, lay)
+    x = H.to_device(x_cpu)
+    k_out, v_out = cq.cq_quantize_kv(lay, x["k"], x["v"])
+    torch.cuda.synchronize()
+    H.assert_qtensor_equal(k_out, kq, what + " keys")
+    H.assert_qtensor_equal(v_out, vq, what + " values")
+
+
+def test_config0_full_size():
+    w = synth.WORKLOADS[0]
+    _run(w, H.layout_of(w), what="config0")
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("group", [32, 64, 128])
+def test_config3_shrunk_sweep(bits, group):
+    # same law as the quantizer-only workload (outliers in keys and values), fewer rows/tokens,
+    # several 128-token tiles per row
+    w = synth.WORKLOADS[3].replace(batch=3, n_kv_heads=2, n_q_heads=2, n_vis=640)
+    _run(w, H.layout_of(w, bits, group, group), what="cfg3 b=%d G=%d" % (bits, group))
+
+
+@pytest.mark.parametrize("idx", [1, 2, 4])
+def test_decode_configs_shrunk(idx):
+    w = synth.WORKLOADS[idx].replace(batch=2, n_kv_heads=2, n_q_heads=2, n_vis=768)
+    _run(w, H.layout_of(w), what="cfg%d" % idx)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_wider_codes(bits):
+    w = synth.WORKLOADS[1].replace(batch=1, n_kv_heads=2, n_q_heads=2, n_vis=256)
+    _run(w, H.layout_of(w, bits, 64, 32), what="b=%d" % bits)
+
+
+@pytest.mark.parametrize("d", [32, 64, 256])
+def test_other_head_dims(d):
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=1, n_q_heads=1, head_dim=d, n_vis=192)
+    _run(w, H.layout_of(w, 2, 64, 32), what="d=%d" % d)
+
+
+def test_swapped_axes_and_whole_sequence_group():
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=2, n_vis=384)
+    # paper-literal: channel-wise keys AND values over the whole sequence
+    _run(w, H.layout_of(w, 1, 384, 384, 0, 0), what="G=n")
+    _run(w, H.layout_of(w, 2, 64, 128, 1, 0), what="token-wise keys, channel-wise values")
+
+
+def test_ties_constants_zeros_and_extremes():
+    w = synth.WORKLOADS[0].replace(n_vis=256)
+    x = synth.make_inputs(w, "cpu", parts=("k", "v"))
+    k, v = x["k"], x["v"]
+    k[0, 0, :128, 0] = 1.5                       # constant group
+    k[0, 0, :128, 1] = 0.0
+    k[0, 0, 5, 1] = -0.0                         # zeros of both signs only
+    k[0, 0, :128, 2] = torch.tensor([0.0, 1.0, 0.5, 0.25] * 32)      # exact midpoint ties (b=1)
+    k[0, 0, :128, 3] = torch.tensor([0.0, 3.0, 0.5, 1.5, 2.5, 1.0, 2.0, 3.0] * 16)  # b=2 ties
+    k[0, 0, :128, 4] = torch.tensor([-65504.0, 65504.0, 6e-8, -6e-8] * 32)  # 41-bit differences
+    k[0, 0, 128:, 6] = -0.0                      # constant negative zero
+    v[0, 0, 0, :] = 2.0                          # constant token
+    v[0, 0, 1, :] = torch.tensor([0.0, 3.0, 0.5, 1.5, 2.5, 1.0, 2.0, 3.0] * 16)
+    v[0, 0, 2, :] = torch.tensor([-0.0, 0.0] * 64)
+    v[0, 0, 3, :] = torch.tensor([60000.0, 1e-4, -1e-4, 0.33] * 32)
+    for bits in (1, 2):
+        _run(w, H.layout_of(w, bits, 128, 128), x, what="edge b=%d" % bits)
+        _run(w, H.layout_of(w, bits, 32, 32), x, what="edge G=32 b=%d" % bits)
+
+
+def test_keys_only_and_values_only():
+    w = synth.WORKLOADS[0].replace(n_vis=256)
+    lay = H.layout_of(w)
+    x_cpu = synth.make_inputs(w, "cpu", parts=("k", "v"))
+    kq, vq = H.oracle_quantize(x_cpu, lay)
+    x = H.to_device(x_cpu)
+    k_out, none = cq.cq_quantize_kv(lay, x["k"], None)
+    assert none is None
+    H.assert_qtensor_equal(k_out, kq, "keys only")
+    none, v_out = cq.cq_quantize_kv(lay, None, x["v"])
+    assert none is None
+    H.assert_qtensor_equal(v_out, vq, "values only")
+
+
+def test_runs_on_a_side_stream():
+    w = synth.WORKLOADS[0].replace(n_vis=512)
+    lay = H.layout_of(w)
+    x_cpu = synth.make_inputs(w, "cpu", parts=("k", "v"))
+    kq, vq = H.oracle_quantize(x_cpu, lay)
+    x = H.to_device(x_cpu)
+    torch.cuda.synchronize()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        k_out, v_out = cq.cq_quantize_kv(lay, x["k"], x["v"])
+    st.synchronize()
+    H.assert_qtensor_equal(k_out, kq, "side stream keys")
+    H.assert_qtensor_equal(v_out, vq, "side stream values")
