@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the CalibQuant hot path on one MI355X.
+
+One "step" is one cq_decode_attn call (logits from the packed 1-bit cache, calibration,
+joint softmax with the fp16 text tail, weighted value sum) over one batch of a synthetic
+InternVL-shaped cache that is already resident in HBM.  The quantizer (cq_quantize_kv)
+that produces the cache is timed in the same run and reported under "quantizer".
+
+Prints ONE JSON line.  `value` = KV tokens attended per second = B*(n_vis+n_text)/t.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(w, bits, k_group, v_group):
+    """Bytes the method has to move for one decode call (workspace traffic is not counted).
+
+    Per visual token per KV head: K codes + K (scale fp32 + min fp16)/k_group tokens per channel
+    + V codes + one (scale, min) pair per v_group channels; per text token per KV head 2*d fp16
+    for K and V; plus q and out.
+    """
+    d = w.head_dim
+    per_vis = 2 * d * bits / 8 + 6.0 * d / k_group + 6.0 * d / v_group
+    per_text = 2 * d * 2
+    rows = w.batch * w.n_kv_heads
+    qo = 2 * w.batch * w.n_q_heads * d * 2
+    return rows * (w.n_vis * per_vis + w.n_text * per_text) + qo, per_vis, per_text
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="index into the workload list")
+    ap.add_argument("--bits", type=int, default=1)
+    ap.add_argument("--group", type=int, default=128)
+    ap.add_argument("--path", choices=["auto", "generic", "tuned"], default="auto")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch (debugging only)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2502_14882_amd import binding as cq
+    from paper_2502_14882_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    cq.lib()    # fail loudly if libcq.so is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cq.cq_set_kernel_path({"auto": cq.CQ_PATH_AUTO, "generic": cq.CQ_PATH_GENERIC,
+                           "tuned": cq.CQ_PATH_TUNED}[args.path])
+
+    w = synth.WORKLOADS[args.config]
+    if args.batch:
+        w = w.replace(batch=args.batch)
+    if w.n_q_heads == w.n_kv_heads and w.n_text == 0:
+        print("config %d is the quantizer-only workload; it is reported under 'quantizer' "
+              "of a decode config" % args.config, file=sys.stderr)
+    lay = cq.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_vis, args.bits,
+                         cq.CQ_AXIS_CHANNEL, cq.CQ_AXIS_TOKEN, args.group, args.group)
+    calib = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    bytes_call, per_vis, per_text = algorithmic_bytes(w, args.bits, args.group, args.group)
+
+    # ---- resident inputs: several independent sets so that no call finds its cache warm
+    n_sets = int(min(32, max(3, math.ceil(800e6 / bytes_call))))
+    sets = []
+    quant_ms = []
+    for i in range(n_sets):
+        x = synth.make_inputs(w, dev, seed=w.seed + 7919 * i)
+        k_q = cq.alloc_qtensor(lay, lay.k_axis, lay.k_group, dev)
+        v_q = cq.alloc_qtensor(lay, lay.v_axis, lay.v_group, dev)
+        for rep in range(2):      # first pass warms up, second is timed
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            cq.cq_quantize_kv(lay, x["k"], x["v"], k_q, v_q)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep == 1:
+                quant_ms.append(e0.elapsed_time(e1))
+        sets.append(dict(q=x["q"], k=k_q, v=v_q, k_text=x["k_text"], v_text=x["v_text"],
+                         out=torch.empty_like(x["q"])))
+        if i == 0:
+            sample0 = {n: x[n][:1].cpu() for n in ("k", "v", "q", "k_text", "v_text")}
+        del x
+    ws = torch.empty(cq.cq_decode_workspace_bytes(lay, w.n_text), dtype=torch.uint8, device=dev)
+
+    def step(i):
+        s = sets[i % n_sets]
+        cq.cq_decode_attn(lay, s["q"], s["k"], s["v"], s["k_text"], s["v_text"], w.n_text, calib,
+                          0.0, s["out"], ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        step(i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    dev_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    med_ms, min_ms = dev_ms[len(dev_ms) // 2], dev_ms[0]
+    mean_ms = sum(dev_ms) / len(dev_ms)
+
+    kv_tokens = w.batch * (w.n_vis + w.n_text)
+    value = kv_tokens / (wall_ms * 1e-3)
+    achieved = bytes_call / (mean_ms * 1e-3) / 1e9
+
+    # quantizer figures (bytes read + written per call)
+    rows = w.batch * w.n_kv_heads
+    q_bytes = rows * w.n_vis * (2 * w.head_dim * 2) + rows * w.n_vis * (per_vis)
+    q_ms = sorted(quant_ms)[len(quant_ms) // 2]
+
+    result = {
+        "metric": "decode_attention_kv_tokens_per_s",
+        "value": value,
+        "unit": "KV tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u1 codes, f16 text/query, f32 accumulate" if args.bits == 1
+                 else "u%d codes, f16 text/query, f32 accumulate" % args.bits,
+        "data": "synthetic",
+        "config": {"workload": "configs[%d] %s" % (args.config, w.name), "batch": w.batch,
+                   "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "n_vis": w.n_vis, "n_text": w.n_text, "bits": args.bits,
+                   "k_group": args.group, "v_group": args.group, "calib": "dynamic tau=(1,2)",
+                   "kernel_path": args.path, "input_sets": n_sets},
+        "device_ms": {"median": med_ms, "min": min_ms, "mean": mean_ms},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "cq_decode_attn (all launches of one call)",
+                     "algorithmic_bytes_per_call": bytes_call,
+                     "bytes_per_visual_token_per_kv_head": per_vis,
+                     "bytes_per_text_token_per_kv_head": per_text},
+        "quantizer": {"ms": q_ms, "bytes_read_plus_written": q_bytes,
+                      "GB/s": q_bytes / (q_ms * 1e-3) / 1e9,
+                      "frac_of_hbm_peak": q_bytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "tokens_per_s": rows * w.n_vis / (q_ms * 1e-3)},
+        "whole_path_500_tokens": {
+            "note": "one quantize + 500 decode steps, as in the paper's overall-throughput column",
+            "sequences_per_s": w.batch / ((q_ms + 500 * mean_ms) * 1e-3)},
+    }
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on one batch item of the same workload (sample of the call)
+        from oracle import cq_oracle as O
+        kq = O.quantize_tensor(sample0["k"].numpy(), args.bits, O.AXIS_CHANNEL, args.group)
+        vq = O.quantize_tensor(sample0["v"].numpy(), args.bits, O.AXIS_TOKEN, args.group)
+        n_rep, t_used = 0, 0.0
+        while t_used < 10.0 and n_rep < 50:
+            c0 = time.perf_counter()
+            ref = O.decode_attn(sample0["q"].numpy(), kq, vq, sample0["k_text"].numpy(),
+                                sample0["v_text"].numpy(), w.n_text, O.CALIB_DYNAMIC, 1.0, 2.0)
+            t_used += time.perf_counter() - c0
+            n_rep += 1
+        out0 = sets[0]["out"]
+        step(0)
+        torch.cuda.synchronize()
+        err = O.rel_l2(out0[:1].cpu().numpy().astype(np.float64), ref)
+        try:
+            import threadpoolctl
+            cores = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        result["cpu_baseline"] = {
+            "value": (w.n_vis + w.n_text) * n_rep / t_used, "unit": "KV tokens/s",
+            "cores": cores, "kind": "oracle",
+            "sample": "batch item 0 of input set 0 (%d of %d sequences), %d repeats, %.1f s"
+                      % (1, w.batch, n_rep, t_used),
+            "host_cpus": os.cpu_count(), "parity_rel_l2_on_sample": err}
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
