@@ -197,10 +197,6 @@ int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* 
     return fail(CQ_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes,
                 wl.total_bytes);
 
-  const int path = g_kernel_path.load();
-  if (path == CQ_PATH_TUNED)
-    return fail(CQ_ERR_UNSUPPORTED, "no tuned decode kernel for this layout");
-
   cq::DecodeShape s;
   s.B = L->batch; s.Hq = L->n_q_heads; s.Hkv = L->n_kv_heads; s.g = s.Hq / s.Hkv;
   s.d = L->head_dim; s.n_vis = L->n_vis; s.n_text = n_text; s.n_text_cap = n_text_cap;
@@ -212,10 +208,20 @@ int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* 
   s.words_per_token = s.d * s.bits / 32;
 
   static const cq_qtensor_t kNone = {nullptr, nullptr, nullptr};
-  hipError_t e = cq::launch_decode_generic(s, q_f16, k ? *k : kNone, v ? *v : kNone, k_text_f16,
-                                           v_text_f16, c, softmax_scale, out_f16,
-                                           static_cast<float*>(workspace), wl,
-                                           static_cast<hipStream_t>(stream));
+  const cq_qtensor_t& kq = k ? *k : kNone;
+  const cq_qtensor_t& vq = v ? *v : kNone;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int path = g_kernel_path.load();
+  const bool tuned_ok = cq::fused_supported(s);
+  if (path == CQ_PATH_TUNED && !tuned_ok)
+    return fail(CQ_ERR_UNSUPPORTED, "no tuned decode kernel for this layout");
+  hipError_t e;
+  if (path != CQ_PATH_GENERIC && tuned_ok)
+    e = cq::launch_decode_fused(s, q_f16, kq, vq, k_text_f16, v_text_f16, c, softmax_scale, out_f16,
+                                st);
+  else
+    e = cq::launch_decode_generic(s, q_f16, kq, vq, k_text_f16, v_text_f16, c, softmax_scale,
+                                  out_f16, static_cast<float*>(workspace), wl, st);
   if (e != hipSuccess) return hip_fail(e, "decode attention");
   return CQ_OK;
 }

@@ -62,6 +62,13 @@ hipError_t launch_decode_generic(const DecodeShape& s, const void* q, const cq_q
                                  const Calib& calib, float softmax_scale, void* out,
                                  float* workspace, const Workspace& wl, hipStream_t stream);
 
+// Fused single-kernel decode for head_dim 128, 1-bit codes, channel-wise keys, per-token values.
+bool fused_supported(const DecodeShape& s);
+hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
+                               const cq_qtensor_t& v, const void* k_text, const void* v_text,
+                               const Calib& calib, float softmax_scale, void* out,
+                               hipStream_t stream);
+
 }  // namespace cq
 
 #endif  // CQ_INTERNAL_H_

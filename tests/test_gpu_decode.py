@@ -17,6 +17,15 @@ import helpers as H
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["generic", "auto"], scope="module")
+def kernel_path(request):
+    """Every case runs twice: on the shape-agnostic kernels and on whatever AUTO selects
+    (the tuned kernels where the layout allows)."""
+    prev = cq.cq_set_kernel_path({"generic": cq.CQ_PATH_GENERIC, "auto": cq.CQ_PATH_AUTO}[request.param])
+    yield request.param
+    cq.cq_set_kernel_path(prev)
+
+
 class Case:
     """Inputs on both sides plus the quantized cache, built once per workload/layout."""
 
@@ -51,7 +60,7 @@ class Case:
 
 
 @pytest.fixture(scope="module")
-def cfg0():
+def cfg0(kernel_path):
     w = synth.WORKLOADS[0]
     return Case(w, H.layout_of(w))
 
@@ -143,3 +152,21 @@ def test_output_is_deterministic(cfg0):
         torch.cuda.synchronize()
         outs.append(o.cpu())
     assert torch.equal(outs[0], outs[1])
+
+
+def test_tuned_path_takes_the_benchmark_layouts(kernel_path):
+    """The layouts of the decode workloads must not fall back silently: forcing the tuned path
+    has to succeed (and agree with the oracle) for them."""
+    if kernel_path != "auto":
+        pytest.skip("runs once")
+    cases = []
+    for w in (synth.WORKLOADS[0],
+              synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8),   # full-length rows
+              synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8)):
+        cases.append(Case(w, H.layout_of(w)))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        for c in cases:
+            c.check()
+    finally:
+        cq.cq_set_kernel_path(prev)
