@@ -123,18 +123,24 @@ int cq_quantize_kv(const cq_layout_t* L, const void* k_f16, const void* v_f16,
   }
   if (L->n_vis == 0) return CQ_OK;
   const int path = g_kernel_path.load();
-  if (path == CQ_PATH_TUNED)
+  const bool k_tuned = cq::quantize_tuned_supported(L->n_vis, L->head_dim, L->bits, L->k_axis, L->k_group);
+  const bool v_tuned = cq::quantize_tuned_supported(L->n_vis, L->head_dim, L->bits, L->v_axis, L->v_group);
+  if (path == CQ_PATH_TUNED && ((do_k && !k_tuned) || (do_v && !v_tuned)))
     return fail(CQ_ERR_UNSUPPORTED, "no tuned quantizer for this layout");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int rows = L->batch * L->n_kv_heads;
   if (do_k) {
-    hipError_t e = cq::launch_quantize_generic(k_f16, *k_out, rows, L->n_vis, L->head_dim, L->bits,
-                                               L->k_axis, L->k_group, s);
+    hipError_t e = (path != CQ_PATH_GENERIC && k_tuned)
+        ? cq::launch_quantize_tuned(k_f16, *k_out, rows, L->n_vis, L->bits, L->k_axis, L->k_group, s)
+        : cq::launch_quantize_generic(k_f16, *k_out, rows, L->n_vis, L->head_dim, L->bits,
+                                      L->k_axis, L->k_group, s);
     if (e != hipSuccess) return hip_fail(e, "quantize keys");
   }
   if (do_v) {
-    hipError_t e = cq::launch_quantize_generic(v_f16, *v_out, rows, L->n_vis, L->head_dim, L->bits,
-                                               L->v_axis, L->v_group, s);
+    hipError_t e = (path != CQ_PATH_GENERIC && v_tuned)
+        ? cq::launch_quantize_tuned(v_f16, *v_out, rows, L->n_vis, L->bits, L->v_axis, L->v_group, s)
+        : cq::launch_quantize_generic(v_f16, *v_out, rows, L->n_vis, L->head_dim, L->bits,
+                                      L->v_axis, L->v_group, s);
     if (e != hipSuccess) return hip_fail(e, "quantize values");
   }
   return CQ_OK;

@@ -1,0 +1,288 @@
+// Tuned quantizer for head_dim 128, b in {1, 2}, groups of 32/64/128 (gfx950).
+//
+// One 256-thread block quantizes a tile of 128 tokens x 128 channels (32 KB of fp16), read once
+// with 16-byte loads and kept in registers:
+//   lane = (token slot lane/16, channel octet lane%16); wave w owns tokens 32w .. 32w+31, so a
+//   wave-wide load is 4 whole token rows = 1 KB contiguous.
+//   1. min/max of Sec. 3.1 with packed-half min/max: over tokens (channel axis: in-thread, then
+//      across the 4 token slots and, for groups > 32 tokens, across waves through LDS) or over
+//      channels (token axis: in-thread over the octet, then across the lanes of a channel group).
+//   2. one thread per (group, channel) resp. (token, channel group) derives, in fp64 where every
+//      quantity is exact, the stored scale/min and 2^b-1 fp16 thresholds t_k such that for every
+//      fp16 x:  x > t_k  <=>  round-half-even((x-min)(2^b-1)/(max-min)) >= k   (Sec. 2.2 equation).
+//   3. codes by comparing packed halves against the thresholds (sign of t - x), bits gathered with
+//      v_perm + v_dot4, words assembled across adjacent lanes, MSB first as in the packing appendix.
+// Results are bit-identical to evaluating the quantize equation element by element in fp64.
+#include <hip/hip_fp16.h>
+
+#include "cq_internal.h"
+
+namespace cq {
+namespace {
+
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+constexpr int kD = 128;
+constexpr int kTile = 128;       // tokens per block
+constexpr int kThreads = 256;
+
+// ---- fp16 bit patterns as an ordered set
+__device__ inline uint16_t h_key(uint16_t u) { return (u & 0x8000u) ? (uint16_t)~u : (uint16_t)(u | 0x8000u); }
+__device__ inline uint16_t h_unkey(uint16_t k) { return (k & 0x8000u) ? (uint16_t)(k & 0x7fffu) : (uint16_t)~k; }
+__device__ inline uint16_t h_next(uint16_t u) { return h_unkey((uint16_t)(h_key(u) + 1)); }
+__device__ inline uint16_t h_prev(uint16_t u) { return h_unkey((uint16_t)(h_key(u) - 1)); }
+__device__ inline double h_to_double(uint16_t u) { return (double)__half2float(__ushort_as_half(u)); }
+
+// Largest fp16 t (as bits) with  NOT [ 2L(t - alpha) ? (2k-1) D ],  ? being > for odd k and >= for
+// even k (the even side of a tie).  Then code >= k  <=>  x > t for every fp16 x.
+__device__ inline uint16_t threshold_bits(double alpha, double D, int k, int L) {
+  if (!(D > 0.0)) return 0x7bffu;            // constant group: nothing exceeds the largest finite
+  const double rhs = (double)(2 * k - 1) * D, twoL = 2.0 * L;
+  const bool strict = (k & 1) != 0;
+  auto pred = [&](uint16_t u) {
+    const double lhs = twoL * (h_to_double(u) - alpha);
+    return strict ? lhs > rhs : lhs >= rhs;
+  };
+  uint16_t t = __half_as_ushort(__float2half_rn((float)(alpha + rhs / twoL)));
+  for (int it = 0; it < 4 && pred(t); ++it) t = h_prev(t);
+  for (int it = 0; it < 4 && !pred(h_next(t)); ++it) t = h_next(t);
+  return t == 0x8000u ? (uint16_t)0 : t;     // -0 would break the sign test against +0
+}
+
+__device__ inline uint16_t canonical_zero(uint16_t bits) { return (bits & 0x7fffu) == 0 ? (uint16_t)0 : bits; }
+
+// sign bits of (t - x) for 8 channels -> 0x80 per channel, channels 0..3 in xa, 4..7 in xb
+__device__ inline void sign_bytes(const v8h& t, const v8h& x, uint32_t& xa, uint32_t& xb) {
+  const v8h d = t - x;
+  const v4u u = __builtin_bit_cast(v4u, d);
+  xa = __builtin_amdgcn_perm(u[1], u[0], 0x07050301u) & 0x80808080u;
+  xb = __builtin_amdgcn_perm(u[3], u[2], 0x07050301u) & 0x80808080u;
+}
+
+// code bits of one octet of one token: 8 bits (b = 1) or 16 bits (b = 2), first channel highest
+template <int BITS>
+__device__ inline uint32_t octet_codes(const v8h& x, const v8h* thr) {
+  if constexpr (BITS == 1) {
+    uint32_t xa, xb;
+    sign_bytes(thr[0], x, xa, xb);
+    const uint32_t s = __builtin_amdgcn_udot4(xa, 0x10204080u, 0u, false);
+    return __builtin_amdgcn_udot4(xb, 0x01020408u, s, false) >> 7;
+  } else {
+    uint32_t a1, b1, a2, b2, a3, b3;
+    sign_bytes(thr[0], x, a1, b1);
+    sign_bytes(thr[1], x, a2, b2);
+    sign_bytes(thr[2], x, a3, b3);
+    const uint32_t la = a1 ^ a2 ^ a3, lb = b1 ^ b2 ^ b3;     // low code bit; high bit is [x > t2]
+    uint32_t up = __builtin_amdgcn_udot4(a2, 0x02082080u, 0u, false);
+    up = __builtin_amdgcn_udot4(la, 0x01041040u, up, false);
+    uint32_t lo = __builtin_amdgcn_udot4(b2, 0x02082080u, 0u, false);
+    lo = __builtin_amdgcn_udot4(lb, 0x01041040u, lo, false);
+    return ((up >> 7) << 8) | (lo >> 7);
+  }
+}
+
+struct QArgs {
+  const __half* x;
+  uint32_t* codes;
+  float* scale;
+  uint16_t* minv;
+};
+
+// AXIS: CQ_AXIS_CHANNEL (GROUP tokens per group) or CQ_AXIS_TOKEN (GROUP channels per group)
+template <int AXIS, int BITS, int GROUP>
+__global__ void __launch_bounds__(kThreads)
+quantize_tile_kernel(const QArgs a) {
+  constexpr int L = (1 << BITS) - 1;
+  constexpr int kWords = kD * BITS / 32;                  // words per token
+  constexpr int NG = AXIS == CQ_AXIS_CHANNEL ? kTile / GROUP : kD / GROUP;   // groups per tile / token
+  __shared__ __align__(16) _Float16 s_part[2][4][kD];     // channel axis: per-wave min, max
+  __shared__ __align__(16) _Float16 s_stat[kTile][4][2];  // token axis: min, max per (token, group)
+  __shared__ __align__(16) _Float16 s_thr[AXIS == CQ_AXIS_CHANNEL ? NG * L * kD : kTile * 4 * 4];
+  __shared__ __align__(16) uint32_t s_codes[kTile * kWords];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c8 = lane & 15, ts = lane >> 4;
+  const size_t tok0 = (size_t)blockIdx.x * kTile;         // tiles never straddle rows (n_vis % 128 == 0)
+  const v8h* src = reinterpret_cast<const v8h*>(a.x) + (tok0 + 32 * wave + ts) * (kD / 8) + c8;
+
+  v8h x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = src[(size_t)i * 4 * (kD / 8)];      // token 32w + 4i + ts
+
+  if constexpr (AXIS == CQ_AXIS_CHANNEL) {
+    // ---- 1. per-channel extrema over the wave's 32 tokens
+    v8h mn = x[0], mx = x[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+      mn = __builtin_elementwise_min(mn, x[i]);
+      mx = __builtin_elementwise_max(mx, x[i]);
+    }
+    v4u mnu = __builtin_bit_cast(v4u, mn), mxu = __builtin_bit_cast(v4u, mx);
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+      v4u on, ox;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        on[r] = __shfl_xor(mnu[r], o);
+        ox[r] = __shfl_xor(mxu[r], o);
+      }
+      mn = __builtin_elementwise_min(mn, __builtin_bit_cast(v8h, on));
+      mx = __builtin_elementwise_max(mx, __builtin_bit_cast(v8h, ox));
+      mnu = __builtin_bit_cast(v4u, mn);
+      mxu = __builtin_bit_cast(v4u, mx);
+    }
+    if (ts == 0) {
+      *reinterpret_cast<v8h*>(&s_part[0][wave][c8 * 8]) = mn;
+      *reinterpret_cast<v8h*>(&s_part[1][wave][c8 * 8]) = mx;
+    }
+    __syncthreads();
+    // ---- 2. one thread per (group, channel): stored parameters and thresholds
+    constexpr int kWavesPerGroup = GROUP / 32;
+    for (int item = tid; item < NG * kD; item += kThreads) {
+      const int g = item / kD, c = item % kD;
+      _Float16 lo = s_part[0][g * kWavesPerGroup][c], hi = s_part[1][g * kWavesPerGroup][c];
+#pragma unroll
+      for (int w = 1; w < kWavesPerGroup; ++w) {
+        lo = (_Float16)fminf((float)lo, (float)s_part[0][g * kWavesPerGroup + w][c]);
+        hi = (_Float16)fmaxf((float)hi, (float)s_part[1][g * kWavesPerGroup + w][c]);
+      }
+      const uint16_t mbits = canonical_zero(__builtin_bit_cast(uint16_t, lo));
+      const double alpha = h_to_double(mbits);
+      const double D = ((double)(float)hi - alpha) + 0.0;
+      const size_t meta = (tok0 / GROUP + g) * kD + c;
+      a.scale[meta] = (float)(D / (double)L);
+      a.minv[meta] = mbits;
+#pragma unroll
+      for (int k = 1; k <= L; ++k)
+        s_thr[(g * L + (k - 1)) * kD + c] =
+            __builtin_bit_cast(_Float16, threshold_bits(alpha, D, k, L));
+    }
+    __syncthreads();
+    // ---- 3. codes
+    const int g = (32 * wave) / GROUP;
+    v8h thr[L];
+#pragma unroll
+    for (int k = 0; k < L; ++k) thr[k] = *reinterpret_cast<const v8h*>(&s_thr[(g * L + k) * kD + c8 * 8]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      uint32_t bits = octet_codes<BITS>(x[i], thr);
+      const int tok = 32 * wave + 4 * i + ts;
+      if constexpr (BITS == 1) {
+        bits <<= 24 - 8 * (c8 & 3);
+        bits |= __shfl_xor(bits, 1);
+        bits |= __shfl_xor(bits, 2);
+        if ((c8 & 3) == 0) s_codes[tok * kWords + (c8 >> 2)] = bits;
+      } else {
+        bits <<= 16 - 16 * (c8 & 1);
+        bits |= __shfl_xor(bits, 1);
+        if ((c8 & 1) == 0) s_codes[tok * kWords + (c8 >> 1)] = bits;
+      }
+    }
+  } else {
+    // ---- 1. per-token extrema over the lanes of a channel group
+    constexpr int kLanesPerGroup = GROUP / 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const v8h xi = x[i];
+      const v4h qa = __builtin_shufflevector(xi, xi, 0, 1, 2, 3);
+      const v4h qb = __builtin_shufflevector(xi, xi, 4, 5, 6, 7);
+      const v4h lo4 = __builtin_elementwise_min(qa, qb), hi4 = __builtin_elementwise_max(qa, qb);
+      const v2h lo = __builtin_elementwise_min(__builtin_shufflevector(lo4, lo4, 0, 1),
+                                               __builtin_shufflevector(lo4, lo4, 2, 3));
+      const v2h hi = __builtin_elementwise_max(__builtin_shufflevector(hi4, hi4, 0, 1),
+                                               __builtin_shufflevector(hi4, hi4, 2, 3));
+      v2h st = {(_Float16)fminf((float)lo[0], (float)lo[1]),
+                (_Float16)(-fmaxf((float)hi[0], (float)hi[1]))};                    // {min, -max}
+#pragma unroll
+      for (int o = 1; o < kLanesPerGroup; o <<= 1) {
+        const uint32_t other = __shfl_xor(__builtin_bit_cast(uint32_t, st), o);
+        st = __builtin_elementwise_min(st, __builtin_bit_cast(v2h, other));
+      }
+      if ((c8 % kLanesPerGroup) == 0) {
+        const int tok = 32 * wave + 4 * i + ts;
+        s_stat[tok][c8 / kLanesPerGroup][0] = st[0];
+        s_stat[tok][c8 / kLanesPerGroup][1] = -st[1];
+      }
+    }
+    __syncthreads();
+    // ---- 2. one thread per (token, channel group)
+    for (int item = tid; item < kTile * NG; item += kThreads) {
+      const int tok = item / NG, g = item % NG;
+      const uint16_t mbits = canonical_zero(__builtin_bit_cast(uint16_t, s_stat[tok][g][0]));
+      const double alpha = h_to_double(mbits);
+      const double D = ((double)(float)s_stat[tok][g][1] - alpha) + 0.0;
+      const size_t meta = (tok0 + tok) * NG + g;
+      a.scale[meta] = (float)(D / (double)L);
+      a.minv[meta] = mbits;
+#pragma unroll
+      for (int k = 1; k <= L; ++k)
+        s_thr[(tok * 4 + g) * 4 + (k - 1)] = __builtin_bit_cast(_Float16, threshold_bits(alpha, D, k, L));
+    }
+    __syncthreads();
+    // ---- 3. codes
+    const int g = c8 / kLanesPerGroup;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int tok = 32 * wave + 4 * i + ts;
+      v8h thr[L];
+#pragma unroll
+      for (int k = 0; k < L; ++k) {
+        const _Float16 t = s_thr[(tok * 4 + g) * 4 + k];
+        thr[k] = (v8h){t, t, t, t, t, t, t, t};
+      }
+      uint32_t bits = octet_codes<BITS>(x[i], thr);
+      if constexpr (BITS == 1) {
+        bits <<= 24 - 8 * (c8 & 3);
+        bits |= __shfl_xor(bits, 1);
+        bits |= __shfl_xor(bits, 2);
+        if ((c8 & 3) == 0) s_codes[tok * kWords + (c8 >> 2)] = bits;
+      } else {
+        bits <<= 16 - 16 * (c8 & 1);
+        bits |= __shfl_xor(bits, 1);
+        if ((c8 & 1) == 0) s_codes[tok * kWords + (c8 >> 1)] = bits;
+      }
+    }
+  }
+  __syncthreads();
+  // ---- the tile's words are contiguous in memory: 16 bytes per thread
+  v4u* dst = reinterpret_cast<v4u*>(a.codes + tok0 * kWords);
+  for (int i = tid; i < kTile * kWords / 4; i += kThreads)
+    dst[i] = *reinterpret_cast<const v4u*>(&s_codes[i * 4]);
+}
+
+template <int AXIS, int BITS>
+hipError_t launch_group(int group, const QArgs& a, unsigned blocks, hipStream_t stream) {
+  switch (group) {
+    case 32: quantize_tile_kernel<AXIS, BITS, 32><<<dim3(blocks), dim3(kThreads), 0, stream>>>(a); break;
+    case 64: quantize_tile_kernel<AXIS, BITS, 64><<<dim3(blocks), dim3(kThreads), 0, stream>>>(a); break;
+    case 128: quantize_tile_kernel<AXIS, BITS, 128><<<dim3(blocks), dim3(kThreads), 0, stream>>>(a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool quantize_tuned_supported(int n_vis, int d, int bits, int axis, int group) {
+  if (d != kD || (bits != 1 && bits != 2)) return false;
+  if (group != 32 && group != 64 && group != 128) return false;
+  if (axis != CQ_AXIS_CHANNEL && axis != CQ_AXIS_TOKEN) return false;
+  return n_vis > 0 && n_vis % kTile == 0;
+}
+
+hipError_t launch_quantize_tuned(const void* x_f16, const cq_qtensor_t& out, int rows, int n_vis,
+                                 int bits, int axis, int group, hipStream_t stream) {
+  const size_t blocks = (size_t)rows * (size_t)(n_vis / kTile);
+  if (blocks > 0x7fffffffu) return hipErrorInvalidConfiguration;
+  const QArgs a{static_cast<const __half*>(x_f16), out.codes, out.scale, out.min};
+  if (axis == CQ_AXIS_CHANNEL)
+    return bits == 1 ? launch_group<CQ_AXIS_CHANNEL, 1>(group, a, (unsigned)blocks, stream)
+                     : launch_group<CQ_AXIS_CHANNEL, 2>(group, a, (unsigned)blocks, stream);
+  return bits == 1 ? launch_group<CQ_AXIS_TOKEN, 1>(group, a, (unsigned)blocks, stream)
+                   : launch_group<CQ_AXIS_TOKEN, 2>(group, a, (unsigned)blocks, stream);
+}
+
+}  // namespace cq

@@ -11,6 +11,14 @@ import helpers as H
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["generic", "auto"], scope="module")
+def kernel_path(request):
+    """Every case runs on the shape-agnostic kernels and on whatever AUTO selects."""
+    prev = cq.cq_set_kernel_path({"generic": cq.CQ_PATH_GENERIC, "auto": cq.CQ_PATH_AUTO}[request.param])
+    yield request.param
+    cq.cq_set_kernel_path(prev)
+
+
 def _run(w, lay, x_cpu=None, what=""):
     x_cpu = x_cpu or synth.make_inputs(w, "cpu", parts=("k", "v"))
     kq, vq = H.oracle_quantize(x_cpu, lay)
@@ -107,3 +115,25 @@ def test_runs_on_a_side_stream():
     st.synchronize()
     H.assert_qtensor_equal(k_out, kq, "side stream keys")
     H.assert_qtensor_equal(v_out, vq, "side stream values")
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("group", [32, 64, 128])
+def test_tuned_path_takes_the_benchmark_layouts(kernel_path, bits, group):
+    """head_dim 128, b in {1,2}, groups 32/64/128 must run on the tuned kernels (no silent
+    fallback) and stay bit-exact, including exact ties and heavy-tailed outliers."""
+    if kernel_path != "auto":
+        pytest.skip("runs once")
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        w = synth.WORKLOADS[4].replace(batch=2, n_kv_heads=2, n_q_heads=2, n_vis=1024)
+        x = synth.make_inputs(w, "cpu", parts=("k", "v"))
+        x["k"][0, 0, :128, 2] = torch.tensor([0.0, 1.0, 0.5, 0.25] * 32)
+        x["k"][0, 0, :128, 3] = torch.tensor([0.0, 3.0, 0.5, 1.5, 2.5, 1.0, 2.0, 3.0] * 16)
+        x["k"][0, 1, :256, 9] = 0.75
+        x["v"][1, 0, 7, :] = torch.tensor([0.0, 3.0, 0.5, 1.5, 2.5, 1.0, 2.0, 3.0] * 16)
+        x["v"][1, 1, 9, :] = -2.5
+        x["v"][1, 1, 10, :] = torch.tensor([-0.0, 0.0] * 64)
+        _run(w, H.layout_of(w, bits, group, group), x, what="tuned b=%d G=%d" % (bits, group))
+    finally:
+        cq.cq_set_kernel_path(prev)
