@@ -145,6 +145,12 @@ int cq_decode_attn(const cq_layout_t *layout, const void *q_f16, const cq_qtenso
 enum { CQ_PATH_AUTO = 0, CQ_PATH_GENERIC = 1, CQ_PATH_TUNED = 2 };
 int cq_set_kernel_path(int path);
 
+/* Measurement aid, not part of the method: enqueue a plain streaming read of `bytes` bytes at
+ * `buf` (device, 16-byte aligned).  `sink` is a device float that is practically never written
+ * (may be NULL).  The benchmark times it to report the practical read ceiling of the box next to
+ * the published HBM peak. */
+int cq_bench_stream_read(const void *buf, size_t bytes, void *sink, void *stream);
+
 /* Text for a cq_status value; never NULL. */
 const char *cq_status_string(int status);
 /* Message of the last failure on this thread ("" if none). */

@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
                                      P(CqCalib), ctypes.c_float, V, V, ctypes.c_size_t, V]
         L.cq_set_kernel_path.restype = ctypes.c_int
         L.cq_set_kernel_path.argtypes = [ctypes.c_int]
+        L.cq_bench_stream_read.restype = ctypes.c_int
+        L.cq_bench_stream_read.argtypes = [V, ctypes.c_size_t, V, V]
         L.cq_status_string.restype = ctypes.c_char_p
         L.cq_status_string.argtypes = [ctypes.c_int]
         L.cq_last_error.restype = ctypes.c_char_p
@@ -178,6 +180,12 @@ def cq_decode_attn(layout: CqLayout, q: torch.Tensor, k: Optional[QTensor], v: O
         ctypes.byref(calib) if calib is not None else None, float(softmax_scale),
         _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(q)))
     return out
+
+
+def cq_bench_stream_read(buf: torch.Tensor, nbytes: int) -> None:
+    """Measurement aid: enqueue a plain streaming read of the first nbytes of buf."""
+    assert nbytes <= buf.numel() * buf.element_size()
+    _check(lib().cq_bench_stream_read(buf.data_ptr(), int(nbytes), None, _stream(buf)))
 
 
 def cq_set_kernel_path(path: int) -> int:
