@@ -193,12 +193,38 @@ def main() -> int:
             reads.append(e0.elapsed_time(e1))
     reads.sort()
     stream_ms = reads[len(reads) // 2]
+    # one plain copy of known size: the launch that byte counters (FETCH_SIZE / WRITE_SIZE) are
+    # scaled with when this command runs under rocprofv3 --pmc
+    cq.cq_bench_stream_copy(probe[nb:], probe, nb)
+    torch.cuda.synchronize()
     del probe
 
     # quantizer figures (bytes read + written per call)
     rows = w.batch * w.n_kv_heads
     q_bytes = rows * w.n_vis * (2 * w.head_dim * 2) + rows * w.n_vis * (per_vis)
     q_ms = sorted(quant_ms)[len(quant_ms) // 2]
+
+    # which kernel ran: forcing the tuned path fails loudly when the layout would fall back
+    prev_path = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        step(0)
+        torch.cuda.synchronize()
+        fused = args.path != "generic"
+    except cq.CqError:
+        fused = False
+    cq.cq_set_kernel_path(prev_path)
+    kernel_name = ("fused_row_kernel<%d> (the call's only launch)" % (args.group // 16) if fused
+                   else "scores_kernel + pv_kernel + combine_kernel (all launches of one call)")
+    traffic = None
+    if fused and args.config == 2 and args.bits == 1 and args.group == 128 and not args.batch:
+        # counter-derived HBM bytes per launch from the committed rocprofv3 summary of this command
+        try:
+            for line in open(os.path.join(ROOT, "profiles",
+                                          "fused_row_kernel_configs2_hbm_traffic.txt")):
+                if line.startswith("fused_row_kernel_configs2_traffic_bytes_per_launch:"):
+                    traffic = float(line.split(":")[1])
+        except OSError:
+            traffic = None
 
     result = {
         "metric": "decode_attention_kv_tokens_per_s",
@@ -221,8 +247,8 @@ def main() -> int:
                    "kernel_path": args.path, "input_sets": n_sets},
         "device_ms": {"median": med_ms, "min": min_ms, "mean": mean_ms},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "cq_decode_attn (all launches of one call)",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": kernel_name,
                      "algorithmic_bytes_per_call": bytes_call,
                      "stream_read_same_bytes": {"ms": stream_ms,
                                                 "GB/s": nb / (stream_ms * 1e-3) / 1e9,

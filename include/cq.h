@@ -150,6 +150,9 @@ int cq_set_kernel_path(int path);
  * (may be NULL).  The benchmark times it to report the practical read ceiling of the box next to
  * the published HBM peak. */
 int cq_bench_stream_read(const void *buf, size_t bytes, void *sink, void *stream);
+/* Measurement aid: plain device-to-device copy of `bytes` bytes (both 16-byte aligned); the
+ * kernel of known traffic that hardware byte counters are scaled with. */
+int cq_bench_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 /* Text for a cq_status value; never NULL. */
 const char *cq_status_string(int status);

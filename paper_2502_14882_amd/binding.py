@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.cq_set_kernel_path.argtypes = [ctypes.c_int]
         L.cq_bench_stream_read.restype = ctypes.c_int
         L.cq_bench_stream_read.argtypes = [V, ctypes.c_size_t, V, V]
+        L.cq_bench_stream_copy.restype = ctypes.c_int
+        L.cq_bench_stream_copy.argtypes = [V, V, ctypes.c_size_t, V]
         L.cq_status_string.restype = ctypes.c_char_p
         L.cq_status_string.argtypes = [ctypes.c_int]
         L.cq_last_error.restype = ctypes.c_char_p
@@ -186,6 +188,11 @@ def cq_bench_stream_read(buf: torch.Tensor, nbytes: int) -> None:
     """Measurement aid: enqueue a plain streaming read of the first nbytes of buf."""
     assert nbytes <= buf.numel() * buf.element_size()
     _check(lib().cq_bench_stream_read(buf.data_ptr(), int(nbytes), None, _stream(buf)))
+
+
+def cq_bench_stream_copy(dst: torch.Tensor, src: torch.Tensor, nbytes: int) -> None:
+    """Measurement aid: enqueue a plain copy of the first nbytes of src to dst."""
+    _check(lib().cq_bench_stream_copy(dst.data_ptr(), src.data_ptr(), int(nbytes), _stream(src)))
 
 
 def cq_set_kernel_path(path: int) -> int:

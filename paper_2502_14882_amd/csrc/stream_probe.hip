@@ -18,7 +18,23 @@ __global__ void __launch_bounds__(256) stream_read_kernel(const v4f* __restrict_
   const float s = (acc[0] + acc[1]) + (acc[2] + acc[3]);
   if (s == 1.2345e-30f && sink) *sink = s;      // keeps the loads alive, practically never true
 }
+__global__ void __launch_bounds__(256) stream_copy_kernel(const v4f* __restrict__ in,
+                                                          v4f* __restrict__ out, size_t n4) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n4; i += stride) out[i] = in[i];
+}
 }  // namespace
+
+extern "C" int cq_bench_stream_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u))
+    return CQ_ERR_NULL;
+  const size_t n4 = bytes / 16;
+  if (n4 == 0) return CQ_OK;
+  stream_copy_kernel<<<dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream)>>>(
+      static_cast<const v4f*>(src), static_cast<v4f*>(dst), n4);
+  return hipGetLastError() == hipSuccess ? CQ_OK : CQ_ERR_HIP;
+}
 
 extern "C" int cq_bench_stream_read(const void* buf, size_t bytes, void* sink, void* stream) {
   if (!buf || (reinterpret_cast<uintptr_t>(buf) & 15u) != 0) return CQ_ERR_NULL;

@@ -170,3 +170,44 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path):
             c.check()
     finally:
         cq.cq_set_kernel_path(prev)
+
+
+def test_full_size_benchmark_config_on_sampled_rows(kernel_path):
+    """configs[2] at full size, drawn on the GPU as bench.py does, through the kernel bench.py
+    times; the oracle checks sampled (batch, KV head) rows, each one independently."""
+    if kernel_path != "auto":
+        pytest.skip("full size runs on the tuned kernels only")
+    w = synth.WORKLOADS[2]
+    lay = H.layout_of(w)
+    x = synth.make_inputs(w, "cuda")
+    k_dev, v_dev = cq.cq_quantize_kv(lay, x["k"], x["v"])
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        out = cq.cq_decode_attn(lay, x["q"], k_dev, v_dev, x["k_text"], x["v_text"], w.n_text,
+                                cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0))
+        torch.cuda.synchronize()
+    finally:
+        cq.cq_set_kernel_path(prev)
+    g = w.n_q_heads // w.n_kv_heads
+    rng = np.random.default_rng(5)
+    rows = {(0, 0), (w.batch - 1, w.n_kv_heads - 1)}
+    while len(rows) < 6:
+        rows.add((int(rng.integers(w.batch)), int(rng.integers(w.n_kv_heads))))
+    for b, h in sorted(rows):
+        k_row = x["k"][b:b + 1, h:h + 1].cpu().numpy()
+        v_row = x["v"][b:b + 1, h:h + 1].cpu().numpy()
+        kq = O.quantize_tensor(k_row, 1, O.AXIS_CHANNEL, 128)
+        vq = O.quantize_tensor(v_row, 1, O.AXIS_TOKEN, 128)
+        assert np.array_equal(H.words_of(k_dev.codes[b:b + 1, h:h + 1]), kq["words"])
+        assert np.array_equal(H.words_of(v_dev.codes[b:b + 1, h:h + 1]), vq["words"])
+        assert np.array_equal(k_dev.scale[b:b + 1, h:h + 1].cpu().numpy().view(np.uint32),
+                              kq["scale"].view(np.uint32))
+        assert np.array_equal(v_dev.min[b:b + 1, h:h + 1].cpu().numpy().view(np.uint16),
+                              vq["min"].view(np.uint16))
+        ref = O.decode_attn(x["q"][b:b + 1, h * g:(h + 1) * g].cpu().numpy(), kq, vq,
+                            x["k_text"][b:b + 1, h:h + 1].cpu().numpy(),
+                            x["v_text"][b:b + 1, h:h + 1].cpu().numpy(), w.n_text,
+                            O.CALIB_DYNAMIC, 1.0, 2.0)
+        got = out[b:b + 1, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)
+        err = O.rel_l2(got, ref)
+        assert err <= H.REL_L2_TOL, "row (%d,%d): rel L2 %.3e" % (b, h, err)
