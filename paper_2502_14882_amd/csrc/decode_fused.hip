@@ -44,7 +44,23 @@ constexpr int kThreads = kWaves * 64;
 constexpr int kHeads = 4;           // query heads per matrix pass (4 digits x 4 heads = 16 rows)
 constexpr int kStageBytes = 2048;   // LDS staging per visual wave
 constexpr int kRedPerHead = 6;
-constexpr int kRing = 4;            // tiles / groups of loads in flight per wave
+// loads in flight per wave, in units of one key group / value tile / text tile / 4 text tokens.
+// Deeper is not better on this chip: with much more than ~32 KB in flight per CU the achieved
+// bandwidth drops (also seen on a plain streaming read).
+#ifndef CQ_RING_K
+#define CQ_RING_K 2
+#endif
+#ifndef CQ_RING_V
+#define CQ_RING_V 2
+#endif
+#ifndef CQ_RING_T
+#define CQ_RING_T 2
+#endif
+#ifndef CQ_RING_TV
+#define CQ_RING_TV 4
+#endif
+constexpr int kRingK = CQ_RING_K, kRingV = CQ_RING_V, kRingT = CQ_RING_T, kRingTV = CQ_RING_TV;
+static_assert(kRingV % 2 == 0, "value tiles alternate between two LDS buffers");
 constexpr float kLog2e = 1.4426950408889634f;
 
 struct FusedArgs {
@@ -84,6 +100,22 @@ __device__ inline float wave_sum(float v) {
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
   return v;
 }
+// Maximum over the wave of a non-negative float, on the DPP network (no LDS round trips); the
+// result is wave-uniform.  Non-negative floats order like their bit patterns.
+__device__ inline float wave_max_nonneg(float v) {
+  int x = __builtin_bit_cast(int, v);
+  x = max(x, __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, true));    // quad_perm 1,0,3,2
+  x = max(x, __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, true));    // quad_perm 2,3,0,1
+  x = max(x, __builtin_amdgcn_update_dpp(x, x, 0x141, 0xF, 0xF, true));   // row_half_mirror
+  x = max(x, __builtin_amdgcn_update_dpp(x, x, 0x140, 0xF, 0xF, true));   // row_mirror
+  x = max(x, __builtin_amdgcn_update_dpp(x, x, 0x142, 0xA, 0xF, false));  // row_bcast15 -> rows 1,3
+  x = max(x, __builtin_amdgcn_update_dpp(x, x, 0x143, 0xC, 0xF, false));  // row_bcast31 -> rows 2,3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(x, 63));
+}
+// value of four signed base-256 digit accumulators
+__device__ inline float digits_to_float(const v4i& c) {
+  return fmaf(fmaf(fmaf((float)c[3], 256.f, (float)c[2]), 256.f, (float)c[1]), 256.f, (float)c[0]);
+}
 __device__ inline void lds_publish() {   // this wave's LDS writes before its later LDS reads
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -91,7 +123,7 @@ __device__ inline void lds_publish() {   // this wave's LDS writes before its la
 
 // Largest F with bound * 2^F <= 2^29, clamped so that 2^(F-7) and 2^-F stay normal floats.
 __device__ inline int fixed_point_shift(float bound) {
-  if (!(bound > 0.f)) return 0;
+  if (!(bound > 0.f)) return 90;
   int e;
   frexpf(bound, &e);           // bound = m * 2^e, m in [0.5, 1)
   return max(-90, min(90, 29 - e));
@@ -127,49 +159,33 @@ fused_row_kernel(const FusedArgs a) {
   // rows of unused heads (g < 4) are computed along but never output; keep them finite
   for (int i = a.g * a.stride + tid; i < kHeads * a.stride; i += kThreads) logits[i] = 0.f;
 
-  // ---- phase 0: query to LDS, fixed-point ranges, additive post-scaling term.
-  // The first batch of every metadata stream is requested before anything waits.
+  // ---- phase 0: query to LDS, max |q| per head, additive post-scaling term q . min_t.
+  // The fixed-point shifts are chosen on the fly in phases 1 and 2 (per key group from the
+  // group's largest scale, per value tile from the largest scale met so far), so the scales are
+  // read exactly once.
   const float* ks_row = a.k_scale + (size_t)row * n_groups * kD;
   const uint16_t* km_row = a.k_min + (size_t)row * n_groups * kD;
   const float* vs_row = a.v_scale + (size_t)row * a.n_vis;
   const uint16_t* vm_row = a.v_min + (size_t)row * a.n_vis;
-  const int N4 = n_groups * (kD / 4), N8 = n_groups * (kD / 8), NV4 = a.n_vis / 4;
-  constexpr int U4 = 3, U8 = 2;
-  v4f ksb[U4], vsb[U4];
+  const int N8 = n_groups * (kD / 8);
+  constexpr int U8 = 2;
   v8h kmb[U8];
   if (a.n_vis > 0) {
-#pragma unroll
-    for (int u = 0; u < U4; ++u) {
-      ksb[u] = *reinterpret_cast<const v4f*>(ks_row + (size_t)min(tid + u * kThreads, N4 - 1) * 4);
-      vsb[u] = *reinterpret_cast<const v4f*>(vs_row + (size_t)min(tid + u * kThreads, NV4 - 1) * 4);
-    }
 #pragma unroll
     for (int u = 0; u < U8; ++u)
       kmb[u] = *reinterpret_cast<const v8h*>(km_row + (size_t)min(tid + u * kThreads, N8 - 1) * 8);
   }
   if (tid < kHeads * kD) {
     const int h = tid / kD, c = tid % kD;
-    qf[tid] = h < a.g ? __half2float(a.q[((size_t)b * a.Hq + (size_t)kvh * a.g + h) * kD + c]) : 0.f;
+    const float qv = h < a.g ? __half2float(a.q[((size_t)b * a.Hq + (size_t)kvh * a.g + h) * kD + c]) : 0.f;
+    qf[tid] = qv;
+    const float m = wave_max_nonneg(fabsf(qv));     // waves 2h, 2h+1 hold head h
+    if (lane == 0) red[wave] = m;
   }
   __syncthreads();
-  float amax[kHeads] = {0.f, 0.f, 0.f, 0.f};
-  for (int base = 0; base < N4; base += U4 * kThreads) {
+  float qmax[kHeads];
 #pragma unroll
-    for (int u = 0; u < U4; ++u) {
-      const int e4 = base + tid + u * kThreads;
-      if (base > 0)
-        ksb[u] = *reinterpret_cast<const v4f*>(ks_row + (size_t)min(e4, N4 - 1) * 4);
-      if (e4 < N4) {
-        const int c = (e4 % (kD / 4)) * 4;
-#pragma unroll
-        for (int h = 0; h < kHeads; ++h) {
-          const v4f qq = *reinterpret_cast<const v4f*>(qf + h * kD + c);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) amax[h] = fmaxf(amax[h], fabsf(qq[i] * ksb[u][i]));
-        }
-      }
-    }
-  }
+  for (int h = 0; h < kHeads; ++h) qmax[h] = fmaxf(red[2 * h], red[2 * h + 1]) * a.softmax_scale;
   for (int base = 0; base < N8; base += U8 * kThreads) {
 #pragma unroll
     for (int u = 0; u < U8; ++u) {
@@ -195,39 +211,7 @@ fused_row_kernel(const FusedArgs a) {
       }
     }
   }
-  float vmax = 0.f;
-  for (int base = 0; base < NV4; base += U4 * kThreads) {
-#pragma unroll
-    for (int u = 0; u < U4; ++u) {
-      const int j4 = base + tid + u * kThreads;
-      if (base > 0)
-        vsb[u] = *reinterpret_cast<const v4f*>(vs_row + (size_t)min(j4, NV4 - 1) * 4);
-      if (j4 < NV4)
-        vmax = fmaxf(fmaxf(vmax, fmaxf(vsb[u][0], vsb[u][1])), fmaxf(vsb[u][2], vsb[u][3]));
-    }
-  }
-#pragma unroll
-  for (int h = 0; h < kHeads; ++h) amax[h] = wave_max(amax[h]);
-  vmax = wave_max(vmax);
-  if (lane == 0) {
-    for (int h = 0; h < kHeads; ++h) red[(wave * kHeads + h) * kRedPerHead + 0] = amax[h];
-    red[(wave * kHeads) * kRedPerHead + 1] = vmax;
-  }
-  __syncthreads();
-  int Fk[kHeads];
-#pragma unroll
-  for (int h = 0; h < kHeads; ++h) {
-    float m = 0.f;
-    for (int w = 0; w < kWaves; ++w) m = fmaxf(m, red[(w * kHeads + h) * kRedPerHead + 0]);
-    Fk[h] = fixed_point_shift(m * a.softmax_scale);
-  }
-  int Fv;
-  {
-    float m = 0.f;
-    for (int w = 0; w < kWaves; ++w) m = fmaxf(m, red[(w * kHeads) * kRedPerHead + 1]);
-    Fv = fixed_point_shift(m);
-  }
-  __syncthreads();   // red is reused below
+  __syncthreads();   // bias complete; red is reused below
   CQ_CLK(1);
 
   // =================================================================== phase 1: logits
@@ -247,11 +231,10 @@ fused_row_kernel(const FusedArgs a) {
       float qv0[kHeads], qv1[kHeads];
 #pragma unroll
       for (int h = 0; h < kHeads; ++h) {
-        const float f = ldexpf(a.softmax_scale, Fk[h] - wp) * (wp == 7 ? -1.f : 1.f);
+        const float f = ldexpf(a.softmax_scale, -wp) * (wp == 7 ? -1.f : 1.f);
         qv0[h] = qf[h * kD + wc0] * f;
         qv1[h] = qf[h * kD + wc1] * f;
       }
-      const float inv_f = ldexpf(1.f, -Fk[hres]);
       const uint32_t* kc_lane = a.k_codes + (size_t)row * a.n_vis * 4 + n16 * 4 + kb;
       float* lrow = logits + (size_t)hres * a.stride + n16;
       // with 128-token groups the operand rows of a group are staged in the group's own logit
@@ -261,8 +244,8 @@ fused_row_kernel(const FusedArgs a) {
       const int x_wr = (lane >> 4) * pitch + ((2 * lane) & 31) * 16;
       const int x_rd = kb * pitch + (n16 >> 1) * 16 + (n16 & 1) * 8;
 
-      uint32_t w[kRing][TILES];
-      float s0[kRing], s1[kRing];
+      uint32_t w[kRingK][TILES];
+      float s0[kRingK], s1[kRingK];
       auto load_group = [&](int slot, int t) {
         const int tc = min(t, n_groups - 1);      // clamped, never a branch around a load
 #pragma unroll
@@ -271,12 +254,19 @@ fused_row_kernel(const FusedArgs a) {
         s1[slot] = ks_row[(size_t)tc * kD + wc1];
       };
       auto do_group = [&](int slot, int t) {
+        // |q'| <= max|q| * (largest scale of the group): a bound, good to a few bits, that costs
+        // one wave-wide maximum instead of a pass over all scales
+        const float smax = wave_max_nonneg(fmaxf(s0[slot], s1[slot]));
+        int Fk[kHeads];
         v4i x0, x1;
 #pragma unroll
         for (int h = 0; h < kHeads; ++h) {
-          x0[h] = signed_digits(__float2int_rn(qv0[h] * s0[slot]));
-          x1[h] = signed_digits(__float2int_rn(qv1[h] * s1[slot]));
+          Fk[h] = fixed_point_shift(qmax[h] * smax);
+          x0[h] = signed_digits(__float2int_rn(ldexpf(qv0[h] * s0[slot], Fk[h])));
+          x1[h] = signed_digits(__float2int_rn(ldexpf(qv1[h] * s1[slot], Fk[h])));
         }
+        const int Fres = hres == 0 ? Fk[0] : hres == 1 ? Fk[1] : hres == 2 ? Fk[2] : Fk[3];
+        const float inv_f = ldexpf(1.f, -Fres);
         uint8_t* xb = kInPlace ? lbytes + (size_t)t * (TILES * 16 * 4) : stage;
         __builtin_amdgcn_wave_barrier();
         *reinterpret_cast<v4i*>(xb + x_wr) = x0;
@@ -312,13 +302,13 @@ fused_row_kernel(const FusedArgs a) {
         }
       };
 #pragma unroll
-      for (int d = 0; d < kRing; ++d) load_group(d, wave + d * kVisWaves);
-      for (int t = wave; t < n_groups; t += kRing * kVisWaves) {
+      for (int d = 0; d < kRingK; ++d) load_group(d, wave + d * kVisWaves);
+      for (int t = wave; t < n_groups; t += kRingK * kVisWaves) {
 #pragma unroll
-        for (int d = 0; d < kRing; ++d) {
+        for (int d = 0; d < kRingK; ++d) {
           const int tt = t + d * kVisWaves;
           if (tt < n_groups) do_group(d, tt);
-          load_group(d, tt + kRing * kVisWaves);
+          load_group(d, tt + kRingK * kVisWaves);
         }
       }
     }
@@ -341,21 +331,23 @@ fused_row_kernel(const FusedArgs a) {
       for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-          At[s][i] = n16 < a.g ? (_Float16)qf[n16 * kD + 32 * kb + 8 * s + i] : (_Float16)0;
-      const __half* kt_row = a.k_text + (size_t)row * a.n_text_cap * kD + 32 * kb;
+          At[s][i] = n16 < a.g ? (_Float16)qf[n16 * kD + 32 * s + 8 * kb + i] : (_Float16)0;
+      // matrix step s takes channels 32s + 8kb .. +7 from lane (n16, kb): the four lanes of a token
+      // read 64 contiguous bytes per load, so a cache line is touched by two loads, not four
+      const __half* kt_row = a.k_text + (size_t)row * a.n_text_cap * kD + 8 * kb;
       const int n_tiles = (a.n_text + 15) / 16;
-      v8h kt[kRing][4];
+      v8h kt[kRingT][4];
       auto load_tile = [&](int slot, int tile) {
         const int tok = min(min(tile, n_tiles - 1) * 16 + n16, a.n_text - 1);
         const v8h* src = reinterpret_cast<const v8h*>(kt_row + (size_t)tok * kD);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kt[slot][s] = src[s];
+        for (int s = 0; s < 4; ++s) kt[slot][s] = src[4 * s];
       };
 #pragma unroll
-      for (int d = 0; d < kRing; ++d) load_tile(d, tw + d * kTextWaves);
-      for (int t = tw; t < n_tiles; t += kRing * kTextWaves) {
+      for (int d = 0; d < kRingT; ++d) load_tile(d, tw + d * kTextWaves);
+      for (int t = tw; t < n_tiles; t += kRingT * kTextWaves) {
 #pragma unroll
-        for (int d = 0; d < kRing; ++d) {
+        for (int d = 0; d < kRingT; ++d) {
           const int tile = t + d * kTextWaves;
           if (tile < n_tiles) {
             v4f c = {0.f, 0.f, 0.f, 0.f};
@@ -375,7 +367,7 @@ fused_row_kernel(const FusedArgs a) {
               }
             }
           }
-          load_tile(d, tile + kRing * kTextWaves);
+          load_tile(d, tile + kRingT * kTextWaves);
         }
       }
     }
@@ -420,6 +412,8 @@ fused_row_kernel(const FusedArgs a) {
 
   // =================================================================== phase 2: weighted values
   v4i acc[8];
+  float facc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // banked part, already unscaled
+  int Fv = 0;          // shift of this wave's accumulators at the end of phase 2
 #pragma unroll
   for (int p = 0; p < 8; ++p) acc[p] = (v4i){0, 0, 0, 0};
   float lsum[kHeads] = {0.f, 0.f, 0.f, 0.f}, msum[kHeads] = {0.f, 0.f, 0.f, 0.f};
@@ -436,18 +430,20 @@ fused_row_kernel(const FusedArgs a) {
       //   P(k)  weights p = 2^(a2*s + c2) from the logits in LDS, their fixed-point digits X(k)
       //         and the raw code bytes back to LDS
       //   M(k)  transposing reads of X(k) and the codes, 8 x (4 AND + 1 MFMA)
-      // One step runs M(k), P(k+1) and G(k+1+kRing); M(k) and P(k+1) are independent, so the
+      // One step runs M(k), P(k+1) and G(k+1+kRingV); M(k) and P(k+1) are independent, so the
       // matrix pipe and the VALU overlap.  X(k) overwrites the tile's own logits (1 KB for
       // 4 heads x 64 tokens, dead once read); the code bytes alternate between two buffers.
-      const float fv = ldexpf(1.f, Fv);
+      // running fixed-point shift: set by the largest value scale met so far; when a tile lowers
+      // it, the integer accumulators are banked into fp32 before that tile is added
+      int F_prep = 90, F_acc = 90, F_tile[2] = {90, 90};
       const uint32_t* vc_row = a.v_codes + (size_t)row * a.n_vis * 4;
       const int step = kVisWaves * 64;
       const int last = a.n_vis - 64;                // first token of the row's last tile
       const int x_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;          // row of token lane
       const int x_rd = (kb * a.stride) * 4 + (n16 >> 1) * 16 + (n16 & 1) * 8;   // tr rows 16kb+k
       const int v_rd = (kb * 16 + (n16 >> 1)) * 16 + (n16 & 1) * 8;
-      v4i cg[kRing];
-      float vsr[kRing], vmr[kRing];
+      v4i cg[kRingV];
+      float vsr[kRingV], vmr[kRingV];
       auto load_tile = [&](int slot, int jt) {
         const int j = min(jt, last) + lane;
         cg[slot] = *reinterpret_cast<const v4i*>(vc_row + (size_t)j * 4);
@@ -455,7 +451,9 @@ fused_row_kernel(const FusedArgs a) {
         vmr[slot] = __half2float(__ushort_as_half(vm_row[j]));
       };
       auto prep_tile = [&](int slot, int jt, int buf) {
-        const float vsf = vsr[slot] * fv;
+        F_prep = min(F_prep, fixed_point_shift(wave_max_nonneg(vsr[slot])));
+        F_tile[buf] = F_prep;
+        const float vsf = ldexpf(vsr[slot], F_prep);
         float lg[kHeads];
 #pragma unroll
         for (int h = 0; h < kHeads; ++h) lg[h] = logits[h * a.stride + jt + lane];
@@ -473,15 +471,15 @@ fused_row_kernel(const FusedArgs a) {
       };
       const int j_first = wave * 64;
 #pragma unroll
-      for (int d = 0; d < kRing; ++d) load_tile(d, j_first + d * step);
+      for (int d = 0; d < kRingV; ++d) load_tile(d, j_first + d * step);
       if (j_first < a.n_vis) {
         prep_tile(0, j_first, 0);
         lds_publish();
       }
-      load_tile(0, j_first + kRing * step);
-      for (int j0 = j_first; j0 < a.n_vis; j0 += kRing * step) {
+      load_tile(0, j_first + kRingV * step);
+      for (int j0 = j_first; j0 < a.n_vis; j0 += kRingV * step) {
 #pragma unroll
-        for (int d = 0; d < kRing; ++d) {
+        for (int d = 0; d < kRingV; ++d) {
           const int jt = j0 + d * step;            // tile handled by M in this step
           if (jt < a.n_vis) {
             const int buf = d & 1;
@@ -491,10 +489,20 @@ fused_row_kernel(const FusedArgs a) {
             const v2i b_lo = lds_read_tr8(vr), b_hi = lds_read_tr8(vr + 128);
             const v4i A = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
             const v4i raw = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
-            constexpr int kNextSlot[kRing] = {1, 2, 3, 0};
-            const int nslot = kNextSlot[d];
+            const int nslot = (d + 1) % kRingV;
             if (jt + step < a.n_vis) prep_tile(nslot, jt + step, buf ^ 1);
-            load_tile(nslot, jt + step + kRing * step);
+            load_tile(nslot, jt + step + kRingV * step);
+            if (F_tile[buf] < F_acc) {              // wave-uniform, rare
+              // a larger scale lowered the shift: bank what was accumulated so far in fp32 (the
+              // four digit accumulators of a value cannot be shifted independently)
+              const float w_old = ldexpf(1.f, -F_acc);
+#pragma unroll
+              for (int p = 0; p < 8; ++p) {
+                facc[p] = fmaf(digits_to_float(acc[p]), w_old, facc[p]);
+                acc[p] = (v4i){0, 0, 0, 0};
+              }
+              F_acc = F_tile[buf];
+            }
 #pragma unroll
             for (int p = 0; p < 8; ++p) {
               v4i B;
@@ -506,6 +514,7 @@ fused_row_kernel(const FusedArgs a) {
           }
         }
       }
+      Fv = F_acc;
     }
     CQ_CLK(4);
   } else {
@@ -517,7 +526,7 @@ fused_row_kernel(const FusedArgs a) {
       const __half* vt_row = a.v_text + (size_t)row * a.n_text_cap * kD + 8 * n16;
       const int n_blocks = (a.n_text + 63) / 64;
       const int p_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;
-      constexpr int kSteps = 16, kDepth = 8;          // 16 wave-wide loads per block, 8 in flight
+      constexpr int kSteps = 16, kDepth = kRingTV;          // 16 wave-wide loads per block, 8 in flight
       v8h ring[kDepth];
       auto load_step = [&](int slot, int blk, int s) {
         const int tok = min(min(blk, n_blocks - 1) * 64 + 4 * s + kb, a.n_text - 1);
@@ -581,10 +590,9 @@ fused_row_kernel(const FusedArgs a) {
     const float inv_fv = ldexpf(1.f, -Fv);
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-      const float v = fmaf(fmaf(fmaf((float)acc[p][3], 256.f, (float)acc[p][2]), 256.f,
-                                (float)acc[p][1]), 256.f, (float)acc[p][0]);
+      const float v = fmaf(digits_to_float(acc[p]), inv_fv, facc[p]);
       const int ch = 32 * (n16 >> 2) + 31 - 8 * (n16 & 3) - p;
-      const float wgt = ldexpf(inv_fv, -p) * (p == 7 ? -1.f : 1.f);
+      const float wgt = ldexpf(1.f, -p) * (p == 7 ? -1.f : 1.f);
       partial[kb * kD + ch] = v * wgt;
     }
   } else if (kb == 0) {
