@@ -218,13 +218,13 @@ int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* 
   const cq_qtensor_t& vq = v ? *v : kNone;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int path = g_kernel_path.load();
-  const bool tuned_ok = cq::fused_supported(s);
+  const bool tuned_ok = cq::fused_supported(s, workspace_bytes);
   if (path == CQ_PATH_TUNED && !tuned_ok)
     return fail(CQ_ERR_UNSUPPORTED, "no tuned decode kernel for this layout");
   hipError_t e;
   if (path != CQ_PATH_GENERIC && tuned_ok)
     e = cq::launch_decode_fused(s, q_f16, kq, vq, k_text_f16, v_text_f16, c, softmax_scale, out_f16,
-                                st);
+                                static_cast<float*>(workspace), workspace_bytes, st);
   else
     e = cq::launch_decode_generic(s, q_f16, kq, vq, k_text_f16, v_text_f16, c, softmax_scale,
                                   out_f16, static_cast<float*>(workspace), wl, st);

@@ -68,12 +68,18 @@ bool quantize_tuned_supported(int n_vis, int d, int bits, int axis, int group);
 hipError_t launch_quantize_tuned(const void* x_f16, const cq_qtensor_t& out, int rows, int n_vis,
                                  int bits, int axis, int group, hipStream_t stream);
 
-// Fused single-kernel decode for head_dim 128, 1-bit codes, channel-wise keys, per-token values.
-bool fused_supported(const DecodeShape& s);
+// Merge the per-chunk partials [n_rows][n_chunks][d + 2] of the online softmax into out.
+hipError_t launch_combine(int n_rows, int n_chunks, int d, const float* partial, void* out,
+                          hipStream_t stream);
+
+// Tuned decode for head_dim 128, 1-bit codes, channel-wise keys, per-token values, g <= 8:
+// one fused launch when a workgroup can own a whole row, else extrema pass + partial pass +
+// combine over chunks of the row (workspace: extrema and partials only).
+bool fused_supported(const DecodeShape& s, size_t workspace_bytes);
 hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
                                const cq_qtensor_t& v, const void* k_text, const void* v_text,
                                const Calib& calib, float softmax_scale, void* out,
-                               hipStream_t stream);
+                               float* workspace, size_t workspace_bytes, hipStream_t stream);
 
 }  // namespace cq
 

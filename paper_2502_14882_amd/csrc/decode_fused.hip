@@ -25,6 +25,7 @@
 #include <hip/hip_fp16.h>
 
 #include <cfloat>
+#include <cstdlib>
 
 #include "cq_internal.h"
 
@@ -62,6 +63,12 @@ constexpr int kRedPerHead = 6;
 constexpr int kRingK = CQ_RING_K, kRingV = CQ_RING_V, kRingT = CQ_RING_T, kRingTV = CQ_RING_TV;
 static_assert(kRingV % 2 == 0, "value tiles alternate between two LDS buffers");
 constexpr float kLog2e = 1.4426950408889634f;
+// kModeFull: the workgroup owns the whole row and writes `out`.  A row that does not fit LDS, has
+// more than 4 query heads per KV head, or belongs to a batch too small to fill the chip is split
+// into chunks: kModeExtrema publishes the extrema of each chunk's visual logits (needed first
+// for the dynamic calibration range), kModePartial recomputes the chunk's logits in LDS and
+// writes one online-softmax partial per (head, chunk) for the combine kernel.
+enum { kModeFull = 0, kModeExtrema = 1, kModePartial = 2 };
 
 struct FusedArgs {
   const __half* q;
@@ -71,6 +78,9 @@ struct FusedArgs {
   __half* out;
   int Hq, Hkv, g, n_vis, n_text, n_text_cap, k_group;
   int stride;        // floats between the logit rows of two heads in LDS
+  int mode, n_chunks, nhb;   // kMode*, chunks per row, blocks of 4 query heads per KV head
+  float* ws_minmax;  // split rows: [B*Hq][n_chunks][2] extrema of the visual logits
+  float* ws_partial; // split rows: [B*Hq][n_chunks][d + 2] partials (m, l, acc) for the combine
   int calib_mode; float tau1, tau2, gamma, delta, softmax_scale;
 #ifdef CQ_PHASE_CLOCKS
   long long* clocks;   // [rows][32] time stamps of the phase boundaries (profiling builds only)
@@ -136,9 +146,25 @@ template <int TILES>
 __global__ void __launch_bounds__(kThreads)
 fused_row_kernel(const FusedArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int row = blockIdx.x;                 // b * Hkv + kvh
+  // workgroup = (row = b * Hkv + kvh, block of 4 query heads, chunk of the row's tokens)
+  const int bid = blockIdx.x;
+  const int chunk = bid % a.n_chunks, hb = (bid / a.n_chunks) % a.nhb;
+  const int row = bid / (a.n_chunks * a.nhb);
   const int b = row / a.Hkv, kvh = row % a.Hkv;
-  const int n_groups = a.n_vis / a.k_group;
+  const int gh = min(kHeads, a.g - hb * kHeads);            // live query heads of this block
+  const size_t head0 = (size_t)b * a.Hq + (size_t)kvh * a.g + (size_t)hb * kHeads;
+  // the chunk's share of the visual tokens (whole key groups and whole 64-token tiles) and of
+  // the 64-token text blocks
+  const int unit = max(1, 64 / a.k_group);
+  const int n_units = a.n_vis / (a.k_group * unit);
+  const int ga = (int)((long long)n_units * chunk / a.n_chunks) * unit;
+  const int gb = (int)((long long)n_units * (chunk + 1) / a.n_chunks) * unit;
+  const int n_groups = gb - ga, nv = n_groups * a.k_group, vis0 = ga * a.k_group;
+  const int n_tblocks = (a.n_text + 63) / 64;
+  const int ba = (int)((long long)n_tblocks * chunk / a.n_chunks);
+  const int bb = (int)((long long)n_tblocks * (chunk + 1) / a.n_chunks);
+  const int txt0 = ba * 64;
+  const int ntx = a.mode == kModeExtrema ? 0 : max(0, min(a.n_text, bb * 64) - txt0);
   const bool vis_wave = wave < kVisWaves;
   const int tw = wave - kVisWaves;            // index among the text waves
   const int n16 = lane & 15, kb = lane >> 4;
@@ -157,27 +183,27 @@ fused_row_kernel(const FusedArgs a) {
   float* red = reinterpret_cast<float*>(smem + off);   // [kWaves][kHeads][kRedPerHead]
 
   // rows of unused heads (g < 4) are computed along but never output; keep them finite
-  for (int i = a.g * a.stride + tid; i < kHeads * a.stride; i += kThreads) logits[i] = 0.f;
+  for (int i = gh * a.stride + tid; i < kHeads * a.stride; i += kThreads) logits[i] = 0.f;
 
   // ---- phase 0: query to LDS, max |q| per head, additive post-scaling term q . min_t.
   // The fixed-point shifts are chosen on the fly in phases 1 and 2 (per key group from the
   // group's largest scale, per value tile from the largest scale met so far), so the scales are
   // read exactly once.
-  const float* ks_row = a.k_scale + (size_t)row * n_groups * kD;
-  const uint16_t* km_row = a.k_min + (size_t)row * n_groups * kD;
-  const float* vs_row = a.v_scale + (size_t)row * a.n_vis;
-  const uint16_t* vm_row = a.v_min + (size_t)row * a.n_vis;
+  const float* ks_row = a.k_scale + ((size_t)row * (a.n_vis / a.k_group) + ga) * kD;
+  const uint16_t* km_row = a.k_min + ((size_t)row * (a.n_vis / a.k_group) + ga) * kD;
+  const float* vs_row = a.v_scale + (size_t)row * a.n_vis + vis0;
+  const uint16_t* vm_row = a.v_min + (size_t)row * a.n_vis + vis0;
   const int N8 = n_groups * (kD / 8);
   constexpr int U8 = 2;
   v8h kmb[U8];
-  if (a.n_vis > 0) {
+  if (nv > 0) {
 #pragma unroll
     for (int u = 0; u < U8; ++u)
       kmb[u] = *reinterpret_cast<const v8h*>(km_row + (size_t)min(tid + u * kThreads, N8 - 1) * 8);
   }
   if (tid < kHeads * kD) {
     const int h = tid / kD, c = tid % kD;
-    const float qv = h < a.g ? __half2float(a.q[((size_t)b * a.Hq + (size_t)kvh * a.g + h) * kD + c]) : 0.f;
+    const float qv = h < gh ? __half2float(a.q[(head0 + h) * kD + c]) : 0.f;
     qf[tid] = qv;
     const float m = wave_max_nonneg(fabsf(qv));     // waves 2h, 2h+1 hold head h
     if (lane == 0) red[wave] = m;
@@ -222,7 +248,7 @@ fused_row_kernel(const FusedArgs a) {
     //   result lane: token n16, head kb (its four digits are the lane's four accumulators)
     const int hres = kb;
     float mn = FLT_MAX, mx = -FLT_MAX;
-    if (a.n_vis > 0) {
+    if (nv > 0) {
       // operand rows: r = ((kb*2 + i)*4 + v)*4 + y  <->  channel 32kb + 31 - (4i+v) - 8y, bit
       // position p = 4i + v.  Row r lives at base + (r / 32) * pitch + (r % 32) * 16.
       const int wi = (lane >> 3) & 1, wv = (lane >> 1) & 3, wy = (lane & 1) * 2;
@@ -235,7 +261,7 @@ fused_row_kernel(const FusedArgs a) {
         qv0[h] = qf[h * kD + wc0] * f;
         qv1[h] = qf[h * kD + wc1] * f;
       }
-      const uint32_t* kc_lane = a.k_codes + (size_t)row * a.n_vis * 4 + n16 * 4 + kb;
+      const uint32_t* kc_lane = a.k_codes + ((size_t)row * a.n_vis + vis0) * 4 + n16 * 4 + kb;
       float* lrow = logits + (size_t)hres * a.stride + n16;
       // with 128-token groups the operand rows of a group are staged in the group's own logit
       // slots (2 KB, not yet written); smaller groups use the wave's staging buffer
@@ -325,20 +351,20 @@ fused_row_kernel(const FusedArgs a) {
   } else {
     // text logits on the fp16 matrix cores (products of fp16 numbers are exact in fp32)
     float tmax[4] = {-FLT_MAX, -FLT_MAX, -FLT_MAX, -FLT_MAX};
-    if (a.n_text > 0) {
+    if (ntx > 0) {
       v8h At[4];
 #pragma unroll
       for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-          At[s][i] = n16 < a.g ? (_Float16)qf[n16 * kD + 32 * s + 8 * kb + i] : (_Float16)0;
+          At[s][i] = n16 < gh ? (_Float16)qf[n16 * kD + 32 * s + 8 * kb + i] : (_Float16)0;
       // matrix step s takes channels 32s + 8kb .. +7 from lane (n16, kb): the four lanes of a token
       // read 64 contiguous bytes per load, so a cache line is touched by two loads, not four
-      const __half* kt_row = a.k_text + (size_t)row * a.n_text_cap * kD + 8 * kb;
-      const int n_tiles = (a.n_text + 15) / 16;
+      const __half* kt_row = a.k_text + ((size_t)row * a.n_text_cap + txt0) * kD + 8 * kb;
+      const int n_tiles = (ntx + 15) / 16;
       v8h kt[kRingT][4];
       auto load_tile = [&](int slot, int tile) {
-        const int tok = min(min(tile, n_tiles - 1) * 16 + n16, a.n_text - 1);
+        const int tok = min(min(tile, n_tiles - 1) * 16 + n16, ntx - 1);
         const v8h* src = reinterpret_cast<const v8h*>(kt_row + (size_t)tok * kD);
 #pragma unroll
         for (int s = 0; s < 4; ++s) kt[slot][s] = src[4 * s];
@@ -355,13 +381,13 @@ fused_row_kernel(const FusedArgs a) {
             for (int s = 0; s < 4; ++s)
               c = __builtin_amdgcn_mfma_f32_16x16x32_f16(At[s], kt[d][s], c, 0, 0, 0);
             const int tok = tile * 16 + n16;
-            if (tok < a.n_text) {     // result rows 4*kb + r are heads; only heads < g exist
+            if (tok < ntx) {     // result rows 4*kb + r are heads; only heads < g exist
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
                 const int h = 4 * kb + r;
-                if (h < a.g) {
+                if (h < gh) {
                   const float sv = c[r] * a.softmax_scale;
-                  logits[h * a.stride + a.n_vis + tok] = sv;
+                  logits[h * a.stride + nv + tok] = sv;
                   tmax[r] = fmaxf(tmax[r], sv);
                 }
               }
@@ -380,9 +406,23 @@ fused_row_kernel(const FusedArgs a) {
   }
   __syncthreads();
   CQ_CLK(3);
+  if (a.mode == kModeExtrema) {
+    // first pass of a split row: only the extrema of this chunk's visual logits are wanted
+    if (tid < gh) {
+      float lo = FLT_MAX, hi = -FLT_MAX;
+      for (int w = 0; w < kVisWaves; ++w) {
+        lo = fminf(lo, red[(w * kHeads + tid) * kRedPerHead + 0]);
+        hi = fmaxf(hi, red[(w * kHeads + tid) * kRedPerHead + 1]);
+      }
+      float* mm = a.ws_minmax + ((head0 + tid) * a.n_chunks + chunk) * 2;
+      mm[0] = lo;
+      mm[1] = hi;
+    }
+    return;
+  }
 
   // ---- phase 2 set-up: calibration line and the softmax reference point, per head
-  float a2[kHeads], c2v[kHeads], c2t[kHeads];
+  float a2[kHeads], c2v[kHeads], c2t[kHeads], mref[kHeads];
 #pragma unroll
   for (int h = 0; h < kHeads; ++h) {
     float lo = FLT_MAX, hi = -FLT_MAX, tm = -FLT_MAX;
@@ -392,19 +432,30 @@ fused_row_kernel(const FusedArgs a) {
     }
     for (int w = kVisWaves; w < kWaves; ++w) tm = fmaxf(tm, red[(w * kHeads + h) * kRedPerHead + 2]);
     float slope = 1.f, gam = 0.f, shift = 0.f;    // s' = slope * (s - gam) + shift
-    if (a.calib_mode != CQ_CALIB_NONE && a.n_vis > 0) {
+    if (a.calib_mode != CQ_CALIB_NONE && nv > 0) {
       float glo = a.gamma, ghi = a.delta;
-      if (a.calib_mode == CQ_CALIB_DYNAMIC) { glo = lo; ghi = hi; }
+      if (a.calib_mode == CQ_CALIB_DYNAMIC) {
+        glo = lo;
+        ghi = hi;
+        if (a.mode == kModePartial && h < gh) {   // extrema of the whole row, from the first pass
+          const float* mm = a.ws_minmax + (head0 + h) * a.n_chunks * 2;
+          for (int cidx = 0; cidx < a.n_chunks; ++cidx) {
+            glo = fminf(glo, mm[2 * cidx]);
+            ghi = fmaxf(ghi, mm[2 * cidx + 1]);
+          }
+        }
+      }
       const float width = ghi - glo;
       slope = width == 0.f ? 1.f : (width + a.tau1 - a.tau2) / width;
       gam = glo;
       shift = glo - a.tau1;
     }
     float M = tm;
-    if (a.n_vis > 0) {
+    if (nv > 0) {
       M = fmaxf(M, slope * (lo - gam) + shift);
       M = fmaxf(M, slope * (hi - gam) + shift);
     }
+    mref[h] = M;
     a2[h] = slope * kLog2e;
     c2v[h] = (shift - slope * gam - M) * kLog2e;
     c2t[h] = -M * kLog2e;
@@ -424,7 +475,7 @@ fused_row_kernel(const FusedArgs a) {
     for (int i = 0; i < 8; ++i) tacc[h][i] = 0.f;
 
   if (vis_wave) {
-    if (a.n_vis > 0) {
+    if (nv > 0) {
       // Pipeline over 64-token tiles (tile k of this wave starts at token (wave + 8k) * 64):
       //   G(k)  global loads of the tile's codes, scale and min into a ring of registers
       //   P(k)  weights p = 2^(a2*s + c2) from the logits in LDS, their fixed-point digits X(k)
@@ -436,9 +487,9 @@ fused_row_kernel(const FusedArgs a) {
       // running fixed-point shift: set by the largest value scale met so far; when a tile lowers
       // it, the integer accumulators are banked into fp32 before that tile is added
       int F_prep = 90, F_acc = 90, F_tile[2] = {90, 90};
-      const uint32_t* vc_row = a.v_codes + (size_t)row * a.n_vis * 4;
+      const uint32_t* vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * 4;
       const int step = kVisWaves * 64;
-      const int last = a.n_vis - 64;                // first token of the row's last tile
+      const int last = nv - 64;                // first token of the row's last tile
       const int x_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;          // row of token lane
       const int x_rd = (kb * a.stride) * 4 + (n16 >> 1) * 16 + (n16 & 1) * 8;   // tr rows 16kb+k
       const int v_rd = (kb * 16 + (n16 >> 1)) * 16 + (n16 & 1) * 8;
@@ -472,16 +523,16 @@ fused_row_kernel(const FusedArgs a) {
       const int j_first = wave * 64;
 #pragma unroll
       for (int d = 0; d < kRingV; ++d) load_tile(d, j_first + d * step);
-      if (j_first < a.n_vis) {
+      if (j_first < nv) {
         prep_tile(0, j_first, 0);
         lds_publish();
       }
       load_tile(0, j_first + kRingV * step);
-      for (int j0 = j_first; j0 < a.n_vis; j0 += kRingV * step) {
+      for (int j0 = j_first; j0 < nv; j0 += kRingV * step) {
 #pragma unroll
         for (int d = 0; d < kRingV; ++d) {
           const int jt = j0 + d * step;            // tile handled by M in this step
-          if (jt < a.n_vis) {
+          if (jt < nv) {
             const int buf = d & 1;
             const uint8_t* xr = lbytes + (size_t)jt * 4 + x_rd;
             const uint8_t* vr = stage + buf * 1024 + v_rd;
@@ -490,7 +541,7 @@ fused_row_kernel(const FusedArgs a) {
             const v4i A = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
             const v4i raw = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
             const int nslot = (d + 1) % kRingV;
-            if (jt + step < a.n_vis) prep_tile(nslot, jt + step, buf ^ 1);
+            if (jt + step < nv) prep_tile(nslot, jt + step, buf ^ 1);
             load_tile(nslot, jt + step + kRingV * step);
             if (F_tile[buf] < F_acc) {              // wave-uniform, rare
               // a larger scale lowered the shift: bank what was accumulated so far in fp32 (the
@@ -522,32 +573,32 @@ fused_row_kernel(const FusedArgs a) {
     // of one token, a wave-wide load covers 4 tokens.  The weights of a 64-token block are
     // computed once (lane = token) and staged in the block's own logit slots.
     float tl[kHeads] = {0.f, 0.f, 0.f, 0.f};
-    if (a.n_text > 0) {
-      const __half* vt_row = a.v_text + (size_t)row * a.n_text_cap * kD + 8 * n16;
-      const int n_blocks = (a.n_text + 63) / 64;
+    if (ntx > 0) {
+      const __half* vt_row = a.v_text + ((size_t)row * a.n_text_cap + txt0) * kD + 8 * n16;
+      const int n_blocks = (ntx + 63) / 64;
       const int p_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;
       constexpr int kSteps = 16, kDepth = kRingTV;          // 16 wave-wide loads per block, 8 in flight
       v8h ring[kDepth];
       auto load_step = [&](int slot, int blk, int s) {
-        const int tok = min(min(blk, n_blocks - 1) * 64 + 4 * s + kb, a.n_text - 1);
+        const int tok = min(min(blk, n_blocks - 1) * 64 + 4 * s + kb, ntx - 1);
         ring[slot] = *reinterpret_cast<const v8h*>(vt_row + (size_t)tok * kD);
       };
 #pragma unroll
       for (int s = 0; s < kDepth; ++s) load_step(s, tw, s);
       for (int blk = tw; blk < n_blocks; blk += kTextWaves) {
         const int t0 = blk * 64;
-        const int nt = min(64, a.n_text - t0);
+        const int nt = min(64, ntx - t0);
         v4f pv = {0.f, 0.f, 0.f, 0.f};
         if (lane < nt) {
 #pragma unroll
           for (int h = 0; h < kHeads; ++h)
-            if (h < a.g)
+            if (h < gh)
               pv[h] = __builtin_amdgcn_exp2f(
-                  fmaf(logits[h * a.stride + a.n_vis + t0 + lane], kLog2e, c2t[h]));
+                  fmaf(logits[h * a.stride + nv + t0 + lane], kLog2e, c2t[h]));
         }
 #pragma unroll
         for (int h = 0; h < kHeads; ++h) tl[h] += pv[h];
-        uint8_t* pb = lbytes + (size_t)(a.n_vis + t0) * 4;
+        uint8_t* pb = lbytes + (size_t)(nv + t0) * 4;
         __builtin_amdgcn_wave_barrier();
         *reinterpret_cast<v4f*>(pb + p_wr) = pv;          // zero beyond nt
         lds_publish();
@@ -608,6 +659,7 @@ fused_row_kernel(const FusedArgs a) {
     if (lane == 0) {
       red[(wave * kHeads + h) * kRedPerHead + 3] = l;
       red[(wave * kHeads + h) * kRedPerHead + 4] = m;
+      if (wave == 0) red[h * kRedPerHead + 5] = mref[h];
     }
   }
   __syncthreads();
@@ -615,14 +667,20 @@ fused_row_kernel(const FusedArgs a) {
   // ---- epilogue: sum the waves, add the additive value term, normalise, round to fp16
   if (tid < kHeads * kD) {
     const int h = tid / kD, c = tid % kD;
-    if (h < a.g) {
+    if (h < gh) {
       float num = 0.f, l = 0.f, m = 0.f;
       for (int w = 0; w < kWaves; ++w) {
         num += reinterpret_cast<float*>(smem)[((size_t)w * kHeads + h) * kD + c];
         l += red[(w * kHeads + h) * kRedPerHead + 3];
         m += red[(w * kHeads + h) * kRedPerHead + 4];
       }
-      a.out[((size_t)b * a.Hq + (size_t)kvh * a.g + h) * kD + c] = __float2half_rn((num + m) / l);
+      if (a.mode == kModeFull) {
+        a.out[(head0 + h) * kD + c] = __float2half_rn((num + m) / l);
+      } else {          // one (m, l, acc[d]) partial of the joint softmax per (head, chunk)
+        float* part = a.ws_partial + ((head0 + h) * a.n_chunks + chunk) * (size_t)(kD + 2);
+        if (c == 0) { part[0] = red[h * kRedPerHead + 5]; part[1] = l; }
+        part[2 + c] = num + m;
+      }
     }
   }
   CQ_CLK(6);
@@ -635,36 +693,107 @@ static long long* g_phase_clocks = nullptr;
 extern "C" void cq_debug_set_phase_clocks(void* p) { g_phase_clocks = static_cast<long long*>(p); }
 #endif
 
-size_t fused_lds_bytes(int g, int n_vis, int n_text, int k_group, int* stride_out) {
+size_t fused_lds_bytes(int n_vis_chunk, int n_text_chunk, int k_group, int* stride_out) {
   // text slots are rounded up to whole 64-token blocks (a block's weights are staged in place)
-  int stride = n_vis + (n_text + 63) / 64 * 64;
+  int stride = n_vis_chunk + (n_text_chunk + 63) / 64 * 64;
   stride += (16 - (stride % 32) + 32) % 32;      // stride = 16 (mod 32): conflict-free head rows
   if (stride_out) *stride_out = stride;
   size_t off = (size_t)kHeads * stride * sizeof(float);
   const size_t part = (size_t)kWaves * kHeads * kD * sizeof(float);
   if (off < part) off = part;
   off += kHeads * kD * sizeof(float);
-  const int n_groups = k_group > 0 ? n_vis / k_group : 0;
+  const int n_groups = k_group > 0 ? n_vis_chunk / k_group : 0;
   off += (size_t)kHeads * (n_groups > 0 ? n_groups : 1) * sizeof(float);
   off = (off + 15) & ~(size_t)15;
   off += (size_t)kVisWaves * kStageBytes;
   off += (size_t)kWaves * kHeads * kRedPerHead * sizeof(float);
-  (void)g;
   return off;
 }
 
-bool fused_supported(const DecodeShape& s) {
-  if (s.d != kD || s.bits != 1) return false;
-  if (s.k_axis != CQ_AXIS_CHANNEL || s.v_axis != CQ_AXIS_TOKEN || s.v_group != kD) return false;
-  if ((s.k_group != 32 && s.k_group != 64 && s.k_group != 128) || s.g > kHeads) return false;
-  if (s.n_vis > 65536 || s.n_vis % 64 != 0) return false;
-  return fused_lds_bytes(s.g, s.n_vis, s.n_text, s.k_group, nullptr) <= 160 * 1024;
+namespace {
+
+struct FusedPlan {
+  bool ok = false;
+  int nhb = 1, n_chunks = 1, stride = 0;
+  size_t lds = 0, ws_minmax_floats = 0, ws_floats = 0;
+};
+
+// largest chunk of a row split into n_chunks (same arithmetic as the kernel)
+void chunk_extent(const DecodeShape& s, int n_chunks, int* nv_max, int* nt_max) {
+  const int unit = 64 / s.k_group > 1 ? 64 / s.k_group : 1;
+  const int n_units = s.n_vis / (s.k_group * unit);
+  const int n_tblocks = (s.n_text + 63) / 64;
+  *nv_max = 0;
+  *nt_max = 0;
+  for (int c = 0; c < n_chunks; ++c) {
+    const int ga = (int)((long long)n_units * c / n_chunks) * unit;
+    const int gb = (int)((long long)n_units * (c + 1) / n_chunks) * unit;
+    const int ba = (int)((long long)n_tblocks * c / n_chunks);
+    const int bb = (int)((long long)n_tblocks * (c + 1) / n_chunks);
+    const int nv = (gb - ga) * s.k_group;
+    int nt = (bb * 64 < s.n_text ? bb * 64 : s.n_text) - ba * 64;
+    if (nt < 0) nt = 0;
+    if (nv > *nv_max) *nv_max = nv;
+    if (nt > *nt_max) *nt_max = nt;
+  }
+}
+
+FusedPlan make_plan(const DecodeShape& s, size_t workspace_bytes) {
+  FusedPlan p;
+  if (s.d != kD || s.bits != 1) return p;
+  if (s.k_axis != CQ_AXIS_CHANNEL || s.v_axis != CQ_AXIS_TOKEN || s.v_group != kD) return p;
+  if (s.k_group != 32 && s.k_group != 64 && s.k_group != 128) return p;
+  if (s.g > 2 * kHeads || s.n_vis % 64 != 0) return p;
+  p.nhb = (s.g + kHeads - 1) / kHeads;
+  const long long rows = (long long)s.B * s.Hkv * p.nhb;
+  const int unit = 64 / s.k_group > 1 ? 64 / s.k_group : 1;
+  const int n_units = s.n_vis / (s.k_group * unit);
+  const int max_chunks = n_units < 64 ? (n_units > 0 ? n_units : 1) : 64;
+  // Fewest chunks that fit LDS.  Splitting a row that fits only to fill idle CUs does not pay:
+  // every chunk repeats the fixed per-workgroup work and the logits are computed twice
+  // (measured on the 128-row configuration: 24 us whole rows, 35 us in 2 chunks, 57 us in 4).
+  int want = 1;
+  (void)rows;
+  if (const char* env = getenv("CQ_DECODE_CHUNKS")) {           // testing / tuning override
+    const int forced = atoi(env);
+    if (forced >= 1) want = forced;
+  }
+  if (want > max_chunks) want = max_chunks;
+  for (int c = want; c <= max_chunks; ++c) {
+    int nv, nt, stride;
+    chunk_extent(s, c, &nv, &nt);
+    const size_t lds = fused_lds_bytes(nv, nt, s.k_group, &stride);
+    if (lds <= 160 * 1024) {
+      p.n_chunks = c;
+      p.stride = stride;
+      p.lds = lds;
+      break;
+    }
+  }
+  if (p.lds == 0) return p;
+  if (p.n_chunks > 1 || p.nhb > 1) {
+    if (s.n_vis == 0) return p;
+    const size_t heads = (size_t)s.B * s.Hq;
+    p.ws_minmax_floats = (heads * p.n_chunks * 2 + 63) / 64 * 64;
+    p.ws_floats = p.ws_minmax_floats + heads * p.n_chunks * (size_t)(kD + 2);
+    if (p.ws_floats * sizeof(float) > workspace_bytes) return p;
+  }
+  p.ok = true;
+  return p;
+}
+
+}  // namespace
+
+bool fused_supported(const DecodeShape& s, size_t workspace_bytes) {
+  return make_plan(s, workspace_bytes).ok;
 }
 
 hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
                                const cq_qtensor_t& v, const void* k_text, const void* v_text,
                                const Calib& calib, float softmax_scale, void* out,
-                               hipStream_t stream) {
+                               float* workspace, size_t workspace_bytes, hipStream_t stream) {
+  const FusedPlan plan = make_plan(s, workspace_bytes);
+  if (!plan.ok) return hipErrorInvalidValue;
   FusedArgs a;
   a.q = static_cast<const __half*>(q);
   a.k_codes = k.codes; a.k_scale = k.scale; a.k_min = k.min;
@@ -676,10 +805,14 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
   a.n_text_cap = s.n_text_cap; a.k_group = s.k_group;
   a.calib_mode = calib.mode; a.tau1 = calib.tau1; a.tau2 = calib.tau2;
   a.gamma = calib.gamma; a.delta = calib.delta; a.softmax_scale = softmax_scale;
+  a.stride = plan.stride;
+  a.n_chunks = plan.n_chunks;
+  a.nhb = plan.nhb;
+  a.ws_minmax = workspace;
+  a.ws_partial = workspace ? workspace + plan.ws_minmax_floats : nullptr;
 #ifdef CQ_PHASE_CLOCKS
   a.clocks = g_phase_clocks;
 #endif
-  const size_t lds = fused_lds_bytes(s.g, s.n_vis, s.n_text, s.k_group, &a.stride);
   void (*kern)(const FusedArgs) = nullptr;
   int slot = 0;
   switch (s.k_group) {
@@ -689,14 +822,31 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
     default: return hipErrorInvalidValue;
   }
   static size_t configured[3] = {0, 0, 0};
-  if (lds > configured[slot]) {
+  if (plan.lds > configured[slot]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan.lds);
     if (e != hipSuccess) return e;
-    configured[slot] = lds;
+    configured[slot] = plan.lds;
   }
-  kern<<<dim3(s.B * s.Hkv), dim3(kThreads), lds, stream>>>(a);
-  return hipGetLastError();
+  const size_t blocks = (size_t)s.B * s.Hkv * plan.nhb * plan.n_chunks;
+  if (blocks > 0x7fffffffu) return hipErrorInvalidConfiguration;
+  const dim3 grid((unsigned)blocks), block(kThreads);
+  if (plan.n_chunks == 1 && plan.nhb == 1) {
+    a.mode = kModeFull;
+    kern<<<grid, block, plan.lds, stream>>>(a);
+    return hipGetLastError();
+  }
+  if (calib.mode == CQ_CALIB_DYNAMIC) {
+    a.mode = kModeExtrema;
+    kern<<<grid, block, plan.lds, stream>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  a.mode = kModePartial;
+  kern<<<grid, block, plan.lds, stream>>>(a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_combine(s.B * s.Hq, plan.n_chunks, kD, a.ws_partial, out, stream);
 }
 
 }  // namespace cq

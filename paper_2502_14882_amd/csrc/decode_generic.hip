@@ -215,6 +215,13 @@ __global__ void combine_kernel(int n_chunks, int d, const float* __restrict__ pa
 
 }  // namespace
 
+hipError_t launch_combine(int n_rows, int n_chunks, int d, const float* partial, void* out,
+                          hipStream_t stream) {
+  combine_kernel<<<dim3((unsigned)n_rows), dim3(d), 0, stream>>>(n_chunks, d, partial,
+                                                                 static_cast<__half*>(out));
+  return hipGetLastError();
+}
+
 hipError_t launch_decode_generic(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
                                  const cq_qtensor_t& v, const void* k_text, const void* v_text,
                                  const Calib& calib, float softmax_scale, void* out,

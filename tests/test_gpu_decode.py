@@ -211,3 +211,25 @@ def test_full_size_benchmark_config_on_sampled_rows(kernel_path):
         got = out[b:b + 1, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)
         err = O.rel_l2(got, ref)
         assert err <= H.REL_L2_TOL, "row (%d,%d): rel L2 %.3e" % (b, h, err)
+
+
+@pytest.mark.parametrize("chunks", [1, 2, 5])
+def test_split_rows_agree_with_whole_rows(kernel_path, chunks, monkeypatch):
+    """The tuned kernel on whole rows (one launch) and on rows split into chunks (extrema pass,
+    partial pass, combine) must both match the oracle; g = 4 and g = 6 (two blocks of heads)."""
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
+    prev = None
+    cases = []
+    for w in (synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200),
+              synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=2560, n_text=130)):
+        cases.append(Case(w, H.layout_of(w)))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        for c in cases:
+            c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+            c.check(cq.CQ_CALIB_NONE)
+            c.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
+    finally:
+        cq.cq_set_kernel_path(prev)
