@@ -141,8 +141,23 @@ __device__ inline int fixed_point_shift(float bound) {
 
 extern __shared__ __align__(16) uint8_t smem[];
 
-// TILES = 16-token tiles per key group (k_group / 16).
-template <int TILES>
+// Masks that turn a packed word into int8 operands, and what an operand byte is worth.
+//   b = 1: variant p in 0..7, mask 0x01010101 << p, byte = bit * 2^p (-128 for p = 7)
+//   b = 2: variant v in 0..3, masks 0x03 / 0x0c / 0x30 per byte and (word >> 2) & 0x30 for the top
+//          code of each byte, byte = code * {1, 4, 16, 16}
+template <int BITS>
+__device__ inline int operand_variant(uint32_t word, int v) {
+  if constexpr (BITS == 1) return (int)(word & (0x01010101u << v));
+  else return v < 3 ? (int)(word & (0x03030303u << (2 * v))) : (int)((word >> 2) & 0x30303030u);
+}
+template <int BITS>
+__device__ inline float variant_weight(int v) {     // 1 / (value of a set code-1 byte)
+  if constexpr (BITS == 1) return ldexpf(1.f, -v) * (v == 7 ? -1.f : 1.f);
+  else return v == 0 ? 1.f : v == 1 ? 0.25f : 0.0625f;
+}
+
+// TILES = 16-token tiles per key group (k_group / 16); BITS = code width (1 or 2).
+template <int TILES, int BITS>
 __global__ void __launch_bounds__(kThreads)
 fused_row_kernel(const FusedArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -249,19 +264,25 @@ fused_row_kernel(const FusedArgs a) {
     const int hres = kb;
     float mn = FLT_MAX, mx = -FLT_MAX;
     if (nv > 0) {
-      // operand rows: r = ((kb*2 + i)*4 + v)*4 + y  <->  channel 32kb + 31 - (4i+v) - 8y, bit
-      // position p = 4i + v.  Row r lives at base + (r / 32) * pitch + (r % 32) * 16.
+      // operand rows: r = ((kb*2 + i)*4 + v)*4 + y, i = matrix, v = register, y = byte.
+      //   b = 1: lane (n16, kb) holds word kb of its token; row r <-> channel
+      //          32kb + 31 - (4i+v) - 8y, mask variant 4i + v;
+      //   b = 2: it holds words 2kb and 2kb+1, matrix i takes word 2kb + i; row r <-> channel
+      //          32kb + 16i + 15 - 4y - v, mask variant v.
+      // Row r lives at base + (r / 32) * pitch + (r % 32) * 16.
       const int wi = (lane >> 3) & 1, wv = (lane >> 1) & 3, wy = (lane & 1) * 2;
-      const int wp = 4 * wi + wv;
-      const int wc0 = 32 * kb + 31 - wp - 8 * wy, wc1 = wc0 - 8;
+      const int wvar = BITS == 1 ? 4 * wi + wv : wv;
+      const int wc0 = BITS == 1 ? 32 * kb + 31 - wvar - 8 * wy : 32 * kb + 16 * wi + 15 - 4 * wy - wv;
+      const int wc1 = wc0 - (BITS == 1 ? 8 : 4);
       float qv0[kHeads], qv1[kHeads];
 #pragma unroll
       for (int h = 0; h < kHeads; ++h) {
-        const float f = ldexpf(a.softmax_scale, -wp) * (wp == 7 ? -1.f : 1.f);
+        const float f = a.softmax_scale * variant_weight<BITS>(wvar);
         qv0[h] = qf[h * kD + wc0] * f;
         qv1[h] = qf[h * kD + wc1] * f;
       }
-      const uint32_t* kc_lane = a.k_codes + ((size_t)row * a.n_vis + vis0) * 4 + n16 * 4 + kb;
+      const uint32_t* kc_lane =
+          a.k_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS) + n16 * (4 * BITS) + kb * BITS;
       float* lrow = logits + (size_t)hres * a.stride + n16;
       // with 128-token groups the operand rows of a group are staged in the group's own logit
       // slots (2 KB, not yet written); smaller groups use the wave's staging buffer
@@ -270,12 +291,15 @@ fused_row_kernel(const FusedArgs a) {
       const int x_wr = (lane >> 4) * pitch + ((2 * lane) & 31) * 16;
       const int x_rd = kb * pitch + (n16 >> 1) * 16 + (n16 & 1) * 8;
 
-      uint32_t w[kRingK][TILES];
+      uint32_t w[kRingK][TILES][BITS];
       float s0[kRingK], s1[kRingK];
       auto load_group = [&](int slot, int t) {
         const int tc = min(t, n_groups - 1);      // clamped, never a branch around a load
 #pragma unroll
-        for (int i = 0; i < TILES; ++i) w[slot][i] = kc_lane[((size_t)tc * TILES + i) * 64];
+        for (int i = 0; i < TILES; ++i)
+#pragma unroll
+          for (int e = 0; e < BITS; ++e)
+            w[slot][i][e] = kc_lane[((size_t)tc * TILES + i) * (64 * BITS) + e];
         s0[slot] = ks_row[(size_t)tc * kD + wc0];
         s1[slot] = ks_row[(size_t)tc * kD + wc1];
       };
@@ -308,12 +332,16 @@ fused_row_kernel(const FusedArgs a) {
         __builtin_amdgcn_wave_barrier();   // operand rows are consumed before logits land there
 #pragma unroll
         for (int tile = 0; tile < TILES; ++tile) {
-          const uint32_t wd = w[slot][tile];
           v4i B0, B1;
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            B0[v] = (int)(wd & (0x01010101u << v));
-            B1[v] = (int)(wd & (0x01010101u << (4 + v)));
+            if constexpr (BITS == 1) {
+              B0[v] = operand_variant<1>(w[slot][tile][0], v);
+              B1[v] = operand_variant<1>(w[slot][tile][0], 4 + v);
+            } else {
+              B0[v] = operand_variant<2>(w[slot][tile][0], v);
+              B1[v] = operand_variant<2>(w[slot][tile][1], v);
+            }
           }
           v4i c = {0, 0, 0, 0};
           c = __builtin_amdgcn_mfma_i32_16x16x64_i8(A0, B0, c, 0, 0, 0);
@@ -487,17 +515,19 @@ fused_row_kernel(const FusedArgs a) {
       // running fixed-point shift: set by the largest value scale met so far; when a tile lowers
       // it, the integer accumulators are banked into fp32 before that tile is added
       int F_prep = 90, F_acc = 90, F_tile[2] = {90, 90};
-      const uint32_t* vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * 4;
+      const uint32_t* vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS);
       const int step = kVisWaves * 64;
       const int last = nv - 64;                // first token of the row's last tile
       const int x_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;          // row of token lane
       const int x_rd = (kb * a.stride) * 4 + (n16 >> 1) * 16 + (n16 & 1) * 8;   // tr rows 16kb+k
-      const int v_rd = (kb * 16 + (n16 >> 1)) * 16 + (n16 & 1) * 8;
-      v4i cg[kRingV];
+      const int v_rd = (kb * 16 + (n16 >> 1)) * (16 * BITS) + (n16 & 1) * 8;
+      v4i cg[kRingV][BITS];
       float vsr[kRingV], vmr[kRingV];
       auto load_tile = [&](int slot, int jt) {
         const int j = min(jt, last) + lane;
-        cg[slot] = *reinterpret_cast<const v4i*>(vc_row + (size_t)j * 4);
+#pragma unroll
+        for (int e = 0; e < BITS; ++e)
+          cg[slot][e] = *reinterpret_cast<const v4i*>(vc_row + (size_t)j * (4 * BITS) + 4 * e);
         vsr[slot] = vs_row[j];
         vmr[slot] = __half2float(__ushort_as_half(vm_row[j]));
       };
@@ -518,7 +548,12 @@ fused_row_kernel(const FusedArgs a) {
         }
         __builtin_amdgcn_wave_barrier();
         *reinterpret_cast<v4i*>(lbytes + (size_t)jt * 4 + x_wr) = xs;
-        *reinterpret_cast<v4i*>(stage + buf * 1024 + lane * 16) = cg[slot];
+        // b = 1: two 1 KB buffers alternate; b = 2: one 2 KB buffer (LDS executes a wave's
+        // accesses in order, so the previous tile's reads are served before these writes)
+#pragma unroll
+        for (int e = 0; e < BITS; ++e)
+          *reinterpret_cast<v4i*>(stage + (BITS == 1 ? buf * 1024 : 0) + lane * (16 * BITS) + 16 * e) =
+              cg[slot][e];
       };
       const int j_first = wave * 64;
 #pragma unroll
@@ -535,11 +570,16 @@ fused_row_kernel(const FusedArgs a) {
           if (jt < nv) {
             const int buf = d & 1;
             const uint8_t* xr = lbytes + (size_t)jt * 4 + x_rd;
-            const uint8_t* vr = stage + buf * 1024 + v_rd;
+            const uint8_t* vr = stage + (BITS == 1 ? buf * 1024 : 0) + v_rd;
             const v2i a_lo = lds_read_tr8(xr), a_hi = lds_read_tr8(xr + 128);
-            const v2i b_lo = lds_read_tr8(vr), b_hi = lds_read_tr8(vr + 128);
             const v4i A = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
-            const v4i raw = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+            // code bytes: column block cb covers bytes 16cb .. 16cb+15 of every token
+            v4i raw[BITS];
+#pragma unroll
+            for (int cb = 0; cb < BITS; ++cb) {
+              const v2i b_lo = lds_read_tr8(vr + 16 * cb), b_hi = lds_read_tr8(vr + 16 * cb + 128 * BITS);
+              raw[cb] = (v4i){b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+            }
             const int nslot = (d + 1) % kRingV;
             if (jt + step < nv) prep_tile(nslot, jt + step, buf ^ 1);
             load_tile(nslot, jt + step + kRingV * step);
@@ -555,10 +595,12 @@ fused_row_kernel(const FusedArgs a) {
               F_acc = F_tile[buf];
             }
 #pragma unroll
-            for (int p = 0; p < 8; ++p) {
+            for (int p = 0; p < 8; ++p) {       // p = mask variant (b = 1) or 4 * block + variant
               v4i B;
 #pragma unroll
-              for (int v = 0; v < 4; ++v) B[v] = raw[v] & (int)(0x01010101u << p);
+              for (int v = 0; v < 4; ++v)
+                B[v] = BITS == 1 ? operand_variant<1>((uint32_t)raw[0][v], p)
+                                 : operand_variant<2>((uint32_t)raw[p >> 2][v], p & 3);
               acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B, acc[p], 0, 0, 0);
             }
             lds_publish();
@@ -642,9 +684,10 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       const float v = fmaf(digits_to_float(acc[p]), inv_fv, facc[p]);
-      const int ch = 32 * (n16 >> 2) + 31 - 8 * (n16 & 3) - p;
-      const float wgt = ldexpf(1.f, -p) * (p == 7 ? -1.f : 1.f);
-      partial[kb * kD + ch] = v * wgt;
+      // column n16 of accumulator p is code byte n16 (b = 1) or 16 * (p / 4) + n16 (b = 2)
+      const int ch = BITS == 1 ? 32 * (n16 >> 2) + 31 - 8 * (n16 & 3) - p
+                               : 64 * (p >> 2) + 16 * (n16 >> 2) + 15 - 4 * (n16 & 3) - (p & 3);
+      partial[kb * kD + ch] = v * variant_weight<BITS>(BITS == 1 ? p : (p & 3));
     }
   } else if (kb == 0) {
 #pragma unroll
@@ -740,7 +783,7 @@ void chunk_extent(const DecodeShape& s, int n_chunks, int* nv_max, int* nt_max) 
 
 FusedPlan make_plan(const DecodeShape& s, size_t workspace_bytes) {
   FusedPlan p;
-  if (s.d != kD || s.bits != 1) return p;
+  if (s.d != kD || (s.bits != 1 && s.bits != 2)) return p;
   if (s.k_axis != CQ_AXIS_CHANNEL || s.v_axis != CQ_AXIS_TOKEN || s.v_group != kD) return p;
   if (s.k_group != 32 && s.k_group != 64 && s.k_group != 128) return p;
   if (s.g > 2 * kHeads || s.n_vis % 64 != 0) return p;
@@ -815,13 +858,16 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
 #endif
   void (*kern)(const FusedArgs) = nullptr;
   int slot = 0;
-  switch (s.k_group) {
-    case 32: kern = fused_row_kernel<2>; slot = 0; break;
-    case 64: kern = fused_row_kernel<4>; slot = 1; break;
-    case 128: kern = fused_row_kernel<8>; slot = 2; break;
+  switch (s.k_group * 4 + s.bits) {
+    case 32 * 4 + 1: kern = fused_row_kernel<2, 1>; slot = 0; break;
+    case 64 * 4 + 1: kern = fused_row_kernel<4, 1>; slot = 1; break;
+    case 128 * 4 + 1: kern = fused_row_kernel<8, 1>; slot = 2; break;
+    case 32 * 4 + 2: kern = fused_row_kernel<2, 2>; slot = 3; break;
+    case 64 * 4 + 2: kern = fused_row_kernel<4, 2>; slot = 4; break;
+    case 128 * 4 + 2: kern = fused_row_kernel<8, 2>; slot = 5; break;
     default: return hipErrorInvalidValue;
   }
-  static size_t configured[3] = {0, 0, 0};
+  static size_t configured[6] = {0, 0, 0, 0, 0, 0};
   if (plan.lds > configured[slot]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan.lds);

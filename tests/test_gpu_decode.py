@@ -164,6 +164,12 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path):
               synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8),   # full-length rows
               synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8)):
         cases.append(Case(w, H.layout_of(w)))
+    # 2-bit codes, and the long-context shape (g = 6, rows split into chunks) at both widths
+    w2 = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8)
+    cases.append(Case(w2, H.layout_of(w2, 2)))
+    w4 = synth.WORKLOADS[4].replace(batch=1, n_kv_heads=1, n_q_heads=6, n_vis=16384, n_text=1024)
+    cases.append(Case(w4, H.layout_of(w4, 1)))
+    cases.append(Case(w4, H.layout_of(w4, 2)))
     prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for c in cases:
