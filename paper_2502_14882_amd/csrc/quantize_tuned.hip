@@ -110,7 +110,8 @@ quantize_tile_kernel(const QArgs a) {
 
   v8h x[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) x[i] = src[(size_t)i * 4 * (kD / 8)];      // token 32w + 4i + ts
+  for (int i = 0; i < 8; ++i)                                              // token 32w + 4i + ts
+    x[i] = __builtin_nontemporal_load(src + (size_t)i * 4 * (kD / 8));   // read exactly once
 
   if constexpr (AXIS == CQ_AXIS_CHANNEL) {
     // ---- 1. per-channel extrema over the wave's 32 tokens
