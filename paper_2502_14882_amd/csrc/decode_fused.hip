@@ -1,4 +1,4 @@
-// Fused decode attention over the packed 1-bit cache for head_dim 128 (gfx950).
+// Fused decode attention over the packed 1- or 2-bit cache for head_dim 128 (gfx950).
 //
 // One workgroup owns one (batch, KV head) row: all of its g query heads, every visual token and
 // the text tail.  The raw logits of the row live in LDS, so the dynamic calibration of Sec. 3.2
@@ -83,24 +83,23 @@ struct FusedArgs {
   float* ws_partial; // split rows: [B*Hq][n_chunks][d + 2] partials (m, l, acc) for the combine
   int calib_mode; float tau1, tau2, gamma, delta, softmax_scale;
 #ifdef CQ_PHASE_CLOCKS
-  long long* clocks;   // [rows][32] time stamps of the phase boundaries (profiling builds only)
+  long long* clocks;   // [rows][64] time stamps of the phase boundaries (profiling builds only)
 #endif
 };
 
 #ifdef CQ_PHASE_CLOCKS
 #define CQ_CLK(k) do { if (lane == 0 && (wave == 0 || wave == kVisWaves) && a.clocks) \
-    a.clocks[(size_t)row * 32 + (wave ? 16 : 0) + (k)] = wall_clock64(); } while (0)
+    a.clocks[(size_t)row * 64 + (wave ? 16 : 0) + (k)] = wall_clock64(); } while (0)
+#define CQ_CLKW(k) do { if (lane == 0 && a.clocks) a.clocks[(size_t)row * 64 + (k) + wave] = wall_clock64(); } while (0)
 #else
 #define CQ_CLK(k) do { } while (0)
+#define CQ_CLKW(k) do { } while (0)
 #endif
 
 __device__ inline v2i lds_read_tr8(const uint8_t* p) {
   return __builtin_amdgcn_ds_read_tr8_b64_v2i32(
       (__attribute__((address_space(3))) v2i*)(p));
 }
-
-// x -> four signed base-256 digits stored as the four bytes of the result.
-__device__ inline int signed_digits(int x) { return (x + 0x00808080) ^ 0x00808080; }
 
 __device__ inline float wave_max(float v) {
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
@@ -126,17 +125,66 @@ __device__ inline float wave_max_nonneg(float v) {
 __device__ inline float digits_to_float(const v4i& c) {
   return fmaf(fmaf(fmaf((float)c[3], 256.f, (float)c[2]), 256.f, (float)c[1]), 256.f, (float)c[0]);
 }
+// Keeps the software pipelines as written: without it the compiler moves a ring's loads across the
+// loop back-edge next to their use, which exposes the full memory latency in every iteration.
+__device__ inline void pin_order() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
 __device__ inline void lds_publish() {   // this wave's LDS writes before its later LDS reads
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
 }
 
-// Largest F with bound * 2^F <= 2^29, clamped so that 2^(F-7) and 2^-F stay normal floats.
+template <int CTRL>
+__device__ inline float dpp_f32(float v) {
+  const int x = __builtin_bit_cast(int, v);
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, true));
+}
+
+// Additive post-scaling term of one key group, sum_c q'[h][c] * min[c] for the four heads.  Every
+// lane brings two channels (q' already carries the softmax scale and the lane's operand weight
+// w, which inv_w = 1/w takes out again).  A transposing butterfly leaves lane (.., b1, b0) with head
+// 2*b0 + b1 after two steps, the remaining steps add lanes that hold the same head; the result
+// lane of head kb = lane / 16 then fetches its head.
+__device__ inline float group_bias(const float (&qv0)[kHeads], const float (&qv1)[kHeads],
+                                   uint16_t m0, uint16_t m1, float inv_w, int lane) {
+  const float f0 = __half2float(__ushort_as_half(m0)) * inv_w;
+  const float f1 = __half2float(__ushort_as_half(m1)) * inv_w;
+  float part[kHeads];
+#pragma unroll
+  for (int h = 0; h < kHeads; ++h) part[h] = fmaf(qv0[h], f0, qv1[h] * f1);
+  const bool b0 = lane & 1, b1 = lane & 2;
+  float u0 = b0 ? part[2] : part[0], u1 = b0 ? part[3] : part[1];
+  const float g0 = b0 ? part[0] : part[2], g1 = b0 ? part[1] : part[3];
+  u0 += dpp_f32<0xB1>(g0);                 // quad_perm 1,0,3,2: lane ^ 1
+  u1 += dpp_f32<0xB1>(g1);
+  float r = b1 ? u1 : u0;
+  const float g2 = b1 ? u0 : u1;
+  r += dpp_f32<0x4E>(g2);                  // quad_perm 2,3,0,1: lane ^ 2
+  r += dpp_f32<0x124>(r);                  // row_ror 4
+  r += dpp_f32<0x128>(r);                  // row_ror 8
+  r += __shfl_xor(r, 16);
+  r += __shfl_xor(r, 32);
+  const int kb = lane >> 4;
+  return __shfl(r, ((kb >> 1) & 1) | ((kb & 1) << 1));
+}
+
+// Fixed-point operands are |x| < 2^29, four signed base-256 digits.  The wide range is needed
+// because one shift serves a whole key group (or value tile): with heavy-tailed channel scales
+// the ordinary channels sit 2^10 or more below the largest one and still need ~16 bits.  At
+// this width truncation (one v_cvt) is as good as rounding: the bias it adds is below 2^-28 of
+// the largest operand per term.
+// Largest F with bound * 2^F <= 2^29, clamped so that 2^F and 2^-F stay normal floats.
 __device__ inline int fixed_point_shift(float bound) {
   if (!(bound > 0.f)) return 90;
   int e;
   frexpf(bound, &e);           // bound = m * 2^e, m in [0.5, 1)
   return max(-90, min(90, 29 - e));
+}
+// the four signed base-256 digits of trunc(a * b), as the four bytes of the result
+__device__ inline int product_digits(float a, float b) {
+  return ((int)(a * b) + 0x00808080) ^ 0x00808080;
 }
 
 extern __shared__ __align__(16) uint8_t smem[];
@@ -191,7 +239,6 @@ fused_row_kernel(const FusedArgs a) {
   size_t off = (size_t)kHeads * a.stride * sizeof(float);
   if (off < (size_t)kWaves * kHeads * kD * sizeof(float)) off = (size_t)kWaves * kHeads * kD * sizeof(float);
   float* qf = reinterpret_cast<float*>(smem + off);   off += kHeads * kD * sizeof(float);
-  float* bias = reinterpret_cast<float*>(smem + off); off += (size_t)kHeads * max(n_groups, 1) * sizeof(float);
   off = (off + 15) & ~(size_t)15;
   uint8_t* stage = smem + off + (size_t)(vis_wave ? wave : 0) * kStageBytes;
   off += (size_t)kVisWaves * kStageBytes;
@@ -200,22 +247,13 @@ fused_row_kernel(const FusedArgs a) {
   // rows of unused heads (g < 4) are computed along but never output; keep them finite
   for (int i = gh * a.stride + tid; i < kHeads * a.stride; i += kThreads) logits[i] = 0.f;
 
-  // ---- phase 0: query to LDS, max |q| per head, additive post-scaling term q . min_t.
-  // The fixed-point shifts are chosen on the fly in phases 1 and 2 (per key group from the
-  // group's largest scale, per value tile from the largest scale met so far), so the scales are
-  // read exactly once.
+  // ---- phase 0: query to LDS and max |q| per head.  The fixed-point shifts and the additive
+  // post-scaling term q . min_t are formed on the fly in phases 1 and 2 from the scales and minima
+  // that the streaming loads bring in anyway, so every parameter is read exactly once.
   const float* ks_row = a.k_scale + ((size_t)row * (a.n_vis / a.k_group) + ga) * kD;
   const uint16_t* km_row = a.k_min + ((size_t)row * (a.n_vis / a.k_group) + ga) * kD;
   const float* vs_row = a.v_scale + (size_t)row * a.n_vis + vis0;
   const uint16_t* vm_row = a.v_min + (size_t)row * a.n_vis + vis0;
-  const int N8 = n_groups * (kD / 8);
-  constexpr int U8 = 2;
-  v8h kmb[U8];
-  if (nv > 0) {
-#pragma unroll
-    for (int u = 0; u < U8; ++u)
-      kmb[u] = *reinterpret_cast<const v8h*>(km_row + (size_t)min(tid + u * kThreads, N8 - 1) * 8);
-  }
   if (tid < kHeads * kD) {
     const int h = tid / kD, c = tid % kD;
     const float qv = h < gh ? __half2float(a.q[(head0 + h) * kD + c]) : 0.f;
@@ -227,32 +265,8 @@ fused_row_kernel(const FusedArgs a) {
   float qmax[kHeads];
 #pragma unroll
   for (int h = 0; h < kHeads; ++h) qmax[h] = fmaxf(red[2 * h], red[2 * h + 1]) * a.softmax_scale;
-  for (int base = 0; base < N8; base += U8 * kThreads) {
-#pragma unroll
-    for (int u = 0; u < U8; ++u) {
-      const int e8 = base + tid + u * kThreads;
-      if (base > 0)
-        kmb[u] = *reinterpret_cast<const v8h*>(km_row + (size_t)min(e8, N8 - 1) * 8);
-      if (e8 < N8) {          // the 16 lanes that share a token group enter together
-        const int t = e8 / (kD / 8), c0 = (e8 % (kD / 8)) * 8;
-        float part[kHeads];
-#pragma unroll
-        for (int h = 0; h < kHeads; ++h) {
-          float sacc = 0.f;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) sacc = fmaf(qf[h * kD + c0 + i], (float)kmb[u][i], sacc);
-          part[h] = sacc;
-        }
-#pragma unroll
-        for (int h = 0; h < kHeads; ++h) {
-          float sacc = part[h];
-          for (int o = 8; o > 0; o >>= 1) sacc += __shfl_xor(sacc, o);
-          if ((lane & 15) == 0) bias[h * n_groups + t] = sacc * a.softmax_scale;
-        }
-      }
-    }
-  }
-  __syncthreads();   // bias complete; red is reused below
+  const float qmax_all = fmaxf(fmaxf(qmax[0], qmax[1]), fmaxf(qmax[2], qmax[3]));
+  __syncthreads();   // red is reused below
   CQ_CLK(1);
 
   // =================================================================== phase 1: logits
@@ -281,6 +295,7 @@ fused_row_kernel(const FusedArgs a) {
         qv0[h] = qf[h * kD + wc0] * f;
         qv1[h] = qf[h * kD + wc1] * f;
       }
+      const float inv_w = 1.f / variant_weight<BITS>(wvar);     // exact: a power of two
       const uint32_t* kc_lane =
           a.k_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS) + n16 * (4 * BITS) + kb * BITS;
       float* lrow = logits + (size_t)hres * a.stride + n16;
@@ -293,6 +308,7 @@ fused_row_kernel(const FusedArgs a) {
 
       uint32_t w[kRingK][TILES][BITS];
       float s0[kRingK], s1[kRingK];
+      uint16_t m0[kRingK], m1[kRingK];
       auto load_group = [&](int slot, int t) {
         const int tc = min(t, n_groups - 1);      // clamped, never a branch around a load
 #pragma unroll
@@ -302,21 +318,22 @@ fused_row_kernel(const FusedArgs a) {
             w[slot][i][e] = kc_lane[((size_t)tc * TILES + i) * (64 * BITS) + e];
         s0[slot] = ks_row[(size_t)tc * kD + wc0];
         s1[slot] = ks_row[(size_t)tc * kD + wc1];
+        m0[slot] = km_row[(size_t)tc * kD + wc0];
+        m1[slot] = km_row[(size_t)tc * kD + wc1];
       };
       auto do_group = [&](int slot, int t) {
         // |q'| <= max|q| * (largest scale of the group): a bound, good to a few bits, that costs
         // one wave-wide maximum instead of a pass over all scales
         const float smax = wave_max_nonneg(fmaxf(s0[slot], s1[slot]));
-        int Fk[kHeads];
+        const int F = fixed_point_shift(qmax_all * smax);      // one shift for the four heads
+        const float s0f = ldexpf(s0[slot], F), s1f = ldexpf(s1[slot], F);
         v4i x0, x1;
 #pragma unroll
         for (int h = 0; h < kHeads; ++h) {
-          Fk[h] = fixed_point_shift(qmax[h] * smax);
-          x0[h] = signed_digits(__float2int_rn(ldexpf(qv0[h] * s0[slot], Fk[h])));
-          x1[h] = signed_digits(__float2int_rn(ldexpf(qv1[h] * s1[slot], Fk[h])));
+          x0[h] = product_digits(qv0[h], s0f);
+          x1[h] = product_digits(qv1[h], s1f);
         }
-        const int Fres = hres == 0 ? Fk[0] : hres == 1 ? Fk[1] : hres == 2 ? Fk[2] : Fk[3];
-        const float inv_f = ldexpf(1.f, -Fres);
+        const float inv_f = ldexpf(1.f, -F), inv_f16 = ldexpf(1.f, 16 - F);
         uint8_t* xb = kInPlace ? lbytes + (size_t)t * (TILES * 16 * 4) : stage;
         __builtin_amdgcn_wave_barrier();
         *reinterpret_cast<v4i*>(xb + x_wr) = x0;
@@ -328,7 +345,7 @@ fused_row_kernel(const FusedArgs a) {
         const v2i r10 = lds_read_tr8(xr + 256), r11 = lds_read_tr8(xr + 384);
         const v4i A0 = {r00[0], r00[1], r01[0], r01[1]};
         const v4i A1 = {r10[0], r10[1], r11[0], r11[1]};
-        const float bias_h = bias[hres * n_groups + t];
+        const float bias_h = group_bias(qv0, qv1, m0[slot], m1[slot], inv_w, lane);
         __builtin_amdgcn_wave_barrier();   // operand rows are consumed before logits land there
 #pragma unroll
         for (int tile = 0; tile < TILES; ++tile) {
@@ -347,7 +364,7 @@ fused_row_kernel(const FusedArgs a) {
           c = __builtin_amdgcn_mfma_i32_16x16x64_i8(A0, B0, c, 0, 0, 0);
           c = __builtin_amdgcn_mfma_i32_16x16x64_i8(A1, B1, c, 0, 0, 0);
           const int lo = c[0] + (c[1] << 8), hi = c[2] + (c[3] << 8);
-          const float sv = fmaf(fmaf((float)hi, 65536.f, (float)lo), inv_f, bias_h);
+          const float sv = fmaf((float)hi, inv_f16, fmaf((float)lo, inv_f, bias_h));
           // lanes of unused heads (hres >= g) see q = 0, finish with sv = 0 and write their own
           // (never read) logit row: no branch in the hot loop
           lrow[(t * TILES + tile) * 16] = sv;
@@ -357,16 +374,24 @@ fused_row_kernel(const FusedArgs a) {
       };
 #pragma unroll
       for (int d = 0; d < kRingK; ++d) load_group(d, wave + d * kVisWaves);
-      for (int t = wave; t < n_groups; t += kRingK * kVisWaves) {
+      pin_order();
+      int t = wave;
+      for (; t + (kRingK - 1) * kVisWaves < n_groups; t += kRingK * kVisWaves) {
 #pragma unroll
-        for (int d = 0; d < kRingK; ++d) {
+        for (int d = 0; d < kRingK; ++d) {          // no branch around the ring's loads
           const int tt = t + d * kVisWaves;
-          if (tt < n_groups) do_group(d, tt);
+          do_group(d, tt);
+          pin_order();
           load_group(d, tt + kRingK * kVisWaves);
+          pin_order();
         }
       }
+#pragma unroll
+      for (int d = 0; d < kRingK; ++d)              // the wave's last groups, already loaded
+        if (t + d * kVisWaves < n_groups) do_group(d, t + d * kVisWaves);
     }
     CQ_CLK(2);
+    CQ_CLKW(32);
     // fold the 16 token lanes of every head
     for (int o = 8; o > 0; o >>= 1) {
       mn = fminf(mn, __shfl_xor(mn, o));
@@ -399,6 +424,7 @@ fused_row_kernel(const FusedArgs a) {
       };
 #pragma unroll
       for (int d = 0; d < kRingT; ++d) load_tile(d, tw + d * kTextWaves);
+      pin_order();
       for (int t = tw; t < n_tiles; t += kRingT * kTextWaves) {
 #pragma unroll
         for (int d = 0; d < kRingT; ++d) {
@@ -421,11 +447,14 @@ fused_row_kernel(const FusedArgs a) {
               }
             }
           }
+          pin_order();
           load_tile(d, tile + kRingT * kTextWaves);
+          pin_order();
         }
       }
     }
     CQ_CLK(2);
+    CQ_CLKW(32);
 #pragma unroll
     for (int r = 0; r < 4; ++r)
       for (int o = 8; o > 0; o >>= 1) tmax[r] = fmaxf(tmax[r], __shfl_xor(tmax[r], o));
@@ -522,19 +551,21 @@ fused_row_kernel(const FusedArgs a) {
       const int x_rd = (kb * a.stride) * 4 + (n16 >> 1) * 16 + (n16 & 1) * 8;   // tr rows 16kb+k
       const int v_rd = (kb * 16 + (n16 >> 1)) * (16 * BITS) + (n16 & 1) * 8;
       v4i cg[kRingV][BITS];
-      float vsr[kRingV], vmr[kRingV];
+      float vsr[kRingV];
+      uint16_t vmr[kRingV];       // raw fp16 bits: converting here would wait for the load at once
       auto load_tile = [&](int slot, int jt) {
         const int j = min(jt, last) + lane;
 #pragma unroll
         for (int e = 0; e < BITS; ++e)
           cg[slot][e] = *reinterpret_cast<const v4i*>(vc_row + (size_t)j * (4 * BITS) + 4 * e);
         vsr[slot] = vs_row[j];
-        vmr[slot] = __half2float(__ushort_as_half(vm_row[j]));
+        vmr[slot] = vm_row[j];
       };
       auto prep_tile = [&](int slot, int jt, int buf) {
         F_prep = min(F_prep, fixed_point_shift(wave_max_nonneg(vsr[slot])));
         F_tile[buf] = F_prep;
         const float vsf = ldexpf(vsr[slot], F_prep);
+        const float vmf = __half2float(__ushort_as_half(vmr[slot]));
         float lg[kHeads];
 #pragma unroll
         for (int h = 0; h < kHeads; ++h) lg[h] = logits[h * a.stride + jt + lane];
@@ -543,8 +574,8 @@ fused_row_kernel(const FusedArgs a) {
         for (int h = 0; h < kHeads; ++h) {
           const float p = __builtin_amdgcn_exp2f(fmaf(lg[h], a2[h], c2v[h]));
           lsum[h] += p;
-          msum[h] = fmaf(p, vmr[slot], msum[h]);
-          xs[h] = signed_digits(__float2int_rn(p * vsf));
+          msum[h] = fmaf(p, vmf, msum[h]);
+          xs[h] = product_digits(p, vsf);
         }
         __builtin_amdgcn_wave_barrier();
         *reinterpret_cast<v4i*>(lbytes + (size_t)jt * 4 + x_wr) = xs;
@@ -563,53 +594,62 @@ fused_row_kernel(const FusedArgs a) {
         lds_publish();
       }
       load_tile(0, j_first + kRingV * step);
-      for (int j0 = j_first; j0 < nv; j0 += kRingV * step) {
+      pin_order();
+      // one step: M(tile jt) with P(next tile) and G(next tile + kRingV) in its shadow.  In the
+      // main loop every step has a next tile, so the body is free of branches around the ring's
+      // loads (the compiler then counts outstanding loads exactly instead of draining them).
+      auto m_step = [&](int jt, int d, bool always_prep) {
+        const int buf = d & 1;
+        const uint8_t* xr = lbytes + (size_t)jt * 4 + x_rd;
+        const uint8_t* vr = stage + (BITS == 1 ? buf * 1024 : 0) + v_rd;
+        const v2i a_lo = lds_read_tr8(xr), a_hi = lds_read_tr8(xr + 128);
+        const v4i A = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+        // code bytes: column block cb covers bytes 16cb .. 16cb+15 of every token
+        v4i raw[BITS];
 #pragma unroll
-        for (int d = 0; d < kRingV; ++d) {
-          const int jt = j0 + d * step;            // tile handled by M in this step
-          if (jt < nv) {
-            const int buf = d & 1;
-            const uint8_t* xr = lbytes + (size_t)jt * 4 + x_rd;
-            const uint8_t* vr = stage + (BITS == 1 ? buf * 1024 : 0) + v_rd;
-            const v2i a_lo = lds_read_tr8(xr), a_hi = lds_read_tr8(xr + 128);
-            const v4i A = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
-            // code bytes: column block cb covers bytes 16cb .. 16cb+15 of every token
-            v4i raw[BITS];
-#pragma unroll
-            for (int cb = 0; cb < BITS; ++cb) {
-              const v2i b_lo = lds_read_tr8(vr + 16 * cb), b_hi = lds_read_tr8(vr + 16 * cb + 128 * BITS);
-              raw[cb] = (v4i){b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
-            }
-            const int nslot = (d + 1) % kRingV;
-            if (jt + step < nv) prep_tile(nslot, jt + step, buf ^ 1);
-            load_tile(nslot, jt + step + kRingV * step);
-            if (F_tile[buf] < F_acc) {              // wave-uniform, rare
-              // a larger scale lowered the shift: bank what was accumulated so far in fp32 (the
-              // four digit accumulators of a value cannot be shifted independently)
-              const float w_old = ldexpf(1.f, -F_acc);
-#pragma unroll
-              for (int p = 0; p < 8; ++p) {
-                facc[p] = fmaf(digits_to_float(acc[p]), w_old, facc[p]);
-                acc[p] = (v4i){0, 0, 0, 0};
-              }
-              F_acc = F_tile[buf];
-            }
-#pragma unroll
-            for (int p = 0; p < 8; ++p) {       // p = mask variant (b = 1) or 4 * block + variant
-              v4i B;
-#pragma unroll
-              for (int v = 0; v < 4; ++v)
-                B[v] = BITS == 1 ? operand_variant<1>((uint32_t)raw[0][v], p)
-                                 : operand_variant<2>((uint32_t)raw[p >> 2][v], p & 3);
-              acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B, acc[p], 0, 0, 0);
-            }
-            lds_publish();
-          }
+        for (int cb = 0; cb < BITS; ++cb) {
+          const v2i b_lo = lds_read_tr8(vr + 16 * cb), b_hi = lds_read_tr8(vr + 16 * cb + 128 * BITS);
+          raw[cb] = (v4i){b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
         }
+        const int nslot = (d + 1) % kRingV;
+        if (always_prep || jt + step < nv) prep_tile(nslot, jt + step, buf ^ 1);
+        pin_order();
+        load_tile(nslot, jt + step + kRingV * step);
+        pin_order();
+        if (F_tile[buf] < F_acc) {              // wave-uniform, rare
+          // a larger scale lowered the shift: bank what was accumulated so far in fp32 (the
+          // four digit accumulators of a value cannot be shifted independently)
+          const float w_old = ldexpf(1.f, -F_acc);
+#pragma unroll
+          for (int p = 0; p < 8; ++p) {
+            facc[p] = fmaf(digits_to_float(acc[p]), w_old, facc[p]);
+            acc[p] = (v4i){0, 0, 0, 0};
+          }
+          F_acc = F_tile[buf];
+        }
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {       // p = mask variant (b = 1) or 4 * block + variant
+          v4i B;
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            B[v] = BITS == 1 ? operand_variant<1>((uint32_t)raw[0][v], p)
+                             : operand_variant<2>((uint32_t)raw[p >> 2][v], p & 3);
+          acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B, acc[p], 0, 0, 0);
+        }
+        lds_publish();
+      };
+      int j0 = j_first;
+      for (; j0 + kRingV * step < nv; j0 += kRingV * step) {     // all kRingV next tiles exist
+#pragma unroll
+        for (int d = 0; d < kRingV; ++d) m_step(j0 + d * step, d, true);
       }
+#pragma unroll
+      for (int d = 0; d < kRingV; ++d)                            // the wave's last 1..kRingV tiles
+        if (j0 + d * step < nv) m_step(j0 + d * step, d, false);
       Fv = F_acc;
     }
     CQ_CLK(4);
+    CQ_CLKW(48);
   } else {
     // text tail.  lane = (token slot kb, channels 8 * n16 .. +7): one 16-byte load covers 8 channels
     // of one token, a wave-wide load covers 4 tokens.  The weights of a 64-token block are
@@ -627,6 +667,7 @@ fused_row_kernel(const FusedArgs a) {
       };
 #pragma unroll
       for (int s = 0; s < kDepth; ++s) load_step(s, tw, s);
+      pin_order();
       for (int blk = tw; blk < n_blocks; blk += kTextWaves) {
         const int t0 = blk * 64;
         const int nt = min(64, ntx - t0);
@@ -657,6 +698,7 @@ fused_row_kernel(const FusedArgs a) {
           // refill: step s + kDepth of this block, or the start of the wave's next block
           if (s + kDepth < kSteps) load_step(slot, blk, s + kDepth);
           else load_step(slot, blk + kTextWaves, s + kDepth - kSteps);
+          pin_order();
         }
       }
       // fold the four token slots
@@ -673,6 +715,7 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
     for (int h = 0; h < kHeads; ++h) lsum[h] = tl[h];
     CQ_CLK(4);
+    CQ_CLKW(48);
   }
   __syncthreads();    // logits are dead from here on; their LDS becomes the partial buffer
   CQ_CLK(5);
@@ -745,8 +788,7 @@ size_t fused_lds_bytes(int n_vis_chunk, int n_text_chunk, int k_group, int* stri
   const size_t part = (size_t)kWaves * kHeads * kD * sizeof(float);
   if (off < part) off = part;
   off += kHeads * kD * sizeof(float);
-  const int n_groups = k_group > 0 ? n_vis_chunk / k_group : 0;
-  off += (size_t)kHeads * (n_groups > 0 ? n_groups : 1) * sizeof(float);
+  (void)k_group;
   off = (off + 15) & ~(size_t)15;
   off += (size_t)kVisWaves * kStageBytes;
   off += (size_t)kWaves * kHeads * kRedPerHead * sizeof(float);
