@@ -79,6 +79,7 @@ struct FusedArgs {
   int Hq, Hkv, g, n_vis, n_text, n_text_cap, k_group;
   int stride;        // floats between the logit rows of two heads in LDS
   int mode, n_chunks, nhb;   // kMode*, chunks per row, blocks of 4 query heads per KV head
+  int n_pieces;              // rows * n_chunks
   float* ws_minmax;  // split rows: [B*Hq][n_chunks][2] extrema of the visual logits
   float* ws_partial; // split rows: [B*Hq][n_chunks][d + 2] partials (m, l, acc) for the combine
   int calib_mode; float tau1, tau2, gamma, delta, softmax_scale;
@@ -210,9 +211,17 @@ __global__ void __launch_bounds__(kThreads)
 fused_row_kernel(const FusedArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // workgroup = (row = b * Hkv + kvh, block of 4 query heads, chunk of the row's tokens)
-  const int bid = blockIdx.x;
-  const int chunk = bid % a.n_chunks, hb = (bid / a.n_chunks) % a.nhb;
-  const int row = bid / (a.n_chunks * a.nhb);
+  // Workgroups are handed to the 8 XCDs round-robin.  With two head blocks per KV head, the two
+  // workgroups that read the same (row, chunk) get block indices 8 apart: same XCD, started
+  // together, so the second one's key/value reads are served by that XCD's L2.
+  int piece = blockIdx.x, hb = 0;           // piece = row * n_chunks + chunk
+  if (a.nhb > 1) {
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    hb = slot % a.nhb;
+    piece = (slot / a.nhb) * 8 + xcd;
+    if (piece >= a.n_pieces) return;        // grid is rounded up to whole groups of 8 pieces
+  }
+  const int chunk = piece % a.n_chunks, row = piece / a.n_chunks;
   const int b = row / a.Hkv, kvh = row % a.Hkv;
   const int gh = min(kHeads, a.g - hb * kHeads);            // live query heads of this block
   const size_t head0 = (size_t)b * a.Hq + (size_t)kvh * a.g + (size_t)hb * kHeads;
@@ -803,6 +812,19 @@ struct FusedPlan {
   size_t lds = 0, ws_minmax_floats = 0, ws_floats = 0;
 };
 
+long long device_cu_count() {
+  static int n_cus = 0;
+  if (n_cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n_cus = v;
+    else
+      return 256;      // no device (host-only checks): the MI355X count
+  }
+  return n_cus;
+}
+
 // largest chunk of a row split into n_chunks (same arithmetic as the kernel)
 void chunk_extent(const DecodeShape& s, int n_chunks, int* nv_max, int* nt_max) {
   const int unit = 64 / s.k_group > 1 ? 64 / s.k_group : 1;
@@ -838,12 +860,12 @@ FusedPlan make_plan(const DecodeShape& s, size_t workspace_bytes) {
   // every chunk repeats the fixed per-workgroup work and the logits are computed twice
   // (measured on the 128-row configuration: 24 us whole rows, 35 us in 2 chunks, 57 us in 4).
   int want = 1;
-  (void)rows;
   if (const char* env = getenv("CQ_DECODE_CHUNKS")) {           // testing / tuning override
     const int forced = atoi(env);
     if (forced >= 1) want = forced;
   }
   if (want > max_chunks) want = max_chunks;
+  const bool forced = want > 1;
   for (int c = want; c <= max_chunks; ++c) {
     int nv, nt, stride;
     chunk_extent(s, c, &nv, &nt);
@@ -856,6 +878,29 @@ FusedPlan make_plan(const DecodeShape& s, size_t workspace_bytes) {
     }
   }
   if (p.lds == 0) return p;
+  if (p.n_chunks > 1 && !forced) {
+    // A row that has to be split anyway: a few more chunks can fill the last round of
+    // workgroups.  Cost of c chunks ~ rounds over the CUs x (tokens per chunk + a fixed cost per
+    // workgroup worth ~1500 tokens).
+    const long long cus = device_cu_count();
+    long long best_cost = -1;
+    int best_c = p.n_chunks;
+    const int c_hi = 3 * p.n_chunks < max_chunks ? 3 * p.n_chunks : max_chunks;
+    for (int c = p.n_chunks; c <= c_hi; ++c) {
+      int nv, nt;
+      chunk_extent(s, c, &nv, &nt);
+      const long long rounds = (rows * c + cus - 1) / cus;
+      const long long cost = rounds * (nv + nt + 1500);
+      if (best_cost < 0 || cost < best_cost) { best_cost = cost; best_c = c; }
+    }
+    if (best_c != p.n_chunks) {
+      int nv, nt, stride;
+      chunk_extent(s, best_c, &nv, &nt);
+      p.n_chunks = best_c;
+      p.lds = fused_lds_bytes(nv, nt, s.k_group, &stride);
+      p.stride = stride;
+    }
+  }
   if (p.n_chunks > 1 || p.nhb > 1) {
     if (s.n_vis == 0) return p;
     const size_t heads = (size_t)s.B * s.Hq;
@@ -916,8 +961,10 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
     if (e != hipSuccess) return e;
     configured[slot] = plan.lds;
   }
-  const size_t blocks = (size_t)s.B * s.Hkv * plan.nhb * plan.n_chunks;
+  const size_t pieces = (size_t)s.B * s.Hkv * plan.n_chunks;
+  const size_t blocks = plan.nhb > 1 ? (pieces + 7) / 8 * 8 * plan.nhb : pieces;
   if (blocks > 0x7fffffffu) return hipErrorInvalidConfiguration;
+  a.n_pieces = (int)pieces;
   const dim3 grid((unsigned)blocks), block(kThreads);
   if (plan.n_chunks == 1 && plan.nhb == 1) {
     a.mode = kModeFull;
