@@ -47,6 +47,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="index into the workload list")
     ap.add_argument("--bits", type=int, default=1)
     ap.add_argument("--group", type=int, default=128)
+    ap.add_argument("--v-axis", choices=["token", "channel"], default="token",
+                    help="value statistics: per token (the benchmark's layout) or per channel over "
+                         "groups of tokens (the paper's own choice)")
     ap.add_argument("--path", choices=["auto", "generic", "tuned"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="override the batch (debugging only)")
@@ -125,7 +128,9 @@ def main() -> int:
             "sweep": sweep}))
         return 0
     lay = cq.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_vis, args.bits,
-                         cq.CQ_AXIS_CHANNEL, cq.CQ_AXIS_TOKEN, args.group, args.group)
+                         cq.CQ_AXIS_CHANNEL,
+                         cq.CQ_AXIS_CHANNEL if args.v_axis == "channel" else cq.CQ_AXIS_TOKEN,
+                         args.group, args.group)
     calib = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
     bytes_call, per_vis, per_text = algorithmic_bytes(w, args.bits, args.group, args.group)
 
@@ -216,7 +221,8 @@ def main() -> int:
     kernel_name = ("fused_row_kernel<%d> (the call's only launch)" % (args.group // 16) if fused
                    else "scores_kernel + pv_kernel + combine_kernel (all launches of one call)")
     traffic = None
-    if fused and args.config == 2 and args.bits == 1 and args.group == 128 and not args.batch:
+    if (fused and args.config == 2 and args.bits == 1 and args.group == 128 and not args.batch
+            and args.v_axis == "token"):
         # counter-derived HBM bytes per launch from the committed rocprofv3 summary of this command
         try:
             for line in open(os.path.join(ROOT, "profiles",
@@ -243,7 +249,8 @@ def main() -> int:
         "config": {"workload": "configs[%d] %s" % (args.config, w.name), "batch": w.batch,
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_vis": w.n_vis, "n_text": w.n_text, "bits": args.bits,
-                   "k_group": args.group, "v_group": args.group, "calib": "dynamic tau=(1,2)",
+                   "k_group": args.group, "v_group": args.group, "v_axis": args.v_axis,
+                   "calib": "dynamic tau=(1,2)",
                    "kernel_path": args.path, "input_sets": n_sets},
         "device_ms": {"median": med_ms, "min": min_ms, "mean": mean_ms},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -77,6 +77,8 @@ struct FusedArgs {
   const __half* k_text; const __half* v_text;
   __half* out;
   int Hq, Hkv, g, n_vis, n_text, n_text_cap, k_group;
+  int v_group;       // channel-wise values: tokens per value group (64 or 128)
+  int unit;          // chunk boundaries are multiples of unit key groups
   int stride;        // floats between the logit rows of two heads in LDS
   int mode, n_chunks, nhb;   // kMode*, chunks per row, blocks of 4 query heads per KV head
   int n_pieces;              // rows * n_chunks
@@ -205,8 +207,10 @@ __device__ inline float variant_weight(int v) {     // 1 / (value of a set code-
   else return v == 0 ? 1.f : v == 1 ? 0.25f : 0.0625f;
 }
 
-// TILES = 16-token tiles per key group (k_group / 16); BITS = code width (1 or 2).
-template <int TILES, int BITS>
+// TILES = 16-token tiles per key group (k_group / 16); BITS = code width (1 or 2); VCH = values
+// quantized channel-wise over groups of tokens (Sec. 3.1, the paper's own choice) instead of
+// token-wise.
+template <int TILES, int BITS, bool VCH>
 __global__ void __launch_bounds__(kThreads)
 fused_row_kernel(const FusedArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -227,7 +231,7 @@ fused_row_kernel(const FusedArgs a) {
   const size_t head0 = (size_t)b * a.Hq + (size_t)kvh * a.g + (size_t)hb * kHeads;
   // the chunk's share of the visual tokens (whole key groups and whole 64-token tiles) and of
   // the 64-token text blocks
-  const int unit = max(1, 64 / a.k_group);
+  const int unit = a.unit;
   const int n_units = a.n_vis / (a.k_group * unit);
   const int ga = (int)((long long)n_units * chunk / a.n_chunks) * unit;
   const int gb = (int)((long long)n_units * (chunk + 1) / a.n_chunks) * unit;
@@ -541,7 +545,133 @@ fused_row_kernel(const FusedArgs a) {
     for (int i = 0; i < 8; ++i) tacc[h][i] = 0.f;
 
   if (vis_wave) {
-    if (nv > 0) {
+    if constexpr (VCH) { if (nv > 0) {
+      // Channel-wise values: out_c = sum over value groups G of
+      //     scale_{G,c} * sum_{j in G} p_j code_{j,c}  +  min_{G,c} * sum_{j in G} p_j.
+      // The weights p_j <= 1 go into the matrix operand with one fixed shift (2^29); an extra
+      // product with an all-ones operand yields sum_j p_j in the same fixed point and in the
+      // accumulator layout (column = code byte, head = lane / 16).  A wave owns whole value
+      // groups (v_group / 64 consecutive tiles) and folds each finished group into fp32.
+      const int VG = a.v_group, tsh = VG == 128 ? 1 : 0, tpg = 1 << tsh;
+      const int n_vg = nv / VG;
+      const int n_my = n_vg > wave ? ((n_vg - wave + kVisWaves - 1) / kVisWaves) << tsh : 0;
+      const uint32_t* vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS);
+      const size_t g0 = (size_t)row * (a.n_vis / VG) + vis0 / VG;
+      // the lane's result columns are code byte n16: 8 (b = 1) or 2 x 4 (b = 2) consecutive channels
+      const int c_lo = BITS == 1 ? 32 * (n16 >> 2) + 24 - 8 * (n16 & 3) : 16 * (n16 >> 2) + 12 - 4 * (n16 & 3);
+      const int c_hi = BITS == 1 ? c_lo + 4 : c_lo + 64;
+      const float* vsc = a.v_scale + g0 * kD;
+      const uint16_t* vmn = a.v_min + g0 * kD;
+      const int x_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;
+      const int x_rd = (kb * a.stride) * 4 + (n16 >> 1) * 16 + (n16 & 1) * 8;
+      const int v_rd = (kb * 16 + (n16 >> 1)) * (16 * BITS) + (n16 & 1) * 8;
+      auto tile_start = [&](int k) {          // k-th tile of this wave, clamped to its last one
+        const int kc = min(k, n_my - 1);
+        return (wave + (kc >> tsh) * kVisWaves) * VG + (kc & (tpg - 1)) * 64;
+      };
+      v4i cg[kRingV][BITS];
+      auto load_tile = [&](int slot, int k) {
+        const int j = tile_start(k) + lane;
+#pragma unroll
+        for (int e = 0; e < BITS; ++e)
+          cg[slot][e] = *reinterpret_cast<const v4i*>(vc_row + (size_t)j * (4 * BITS) + 4 * e);
+      };
+      v4f gsc[2];
+      v2i gmn[2];
+      auto load_group = [&](int gi) {         // scales and minima of the wave's gi-th group
+        const int grp = min(wave + gi * kVisWaves, n_vg - 1);
+        gsc[0] = *reinterpret_cast<const v4f*>(vsc + (size_t)grp * kD + c_lo);
+        gsc[1] = *reinterpret_cast<const v4f*>(vsc + (size_t)grp * kD + c_hi);
+        gmn[0] = *reinterpret_cast<const v2i*>(vmn + (size_t)grp * kD + c_lo);
+        gmn[1] = *reinterpret_cast<const v2i*>(vmn + (size_t)grp * kD + c_hi);
+      };
+      auto prep_tile = [&](int slot, int k, int buf) {
+        const int jt = tile_start(k);
+        float lg[kHeads];
+#pragma unroll
+        for (int h = 0; h < kHeads; ++h) lg[h] = logits[h * a.stride + jt + lane];
+        v4i xs;
+#pragma unroll
+        for (int h = 0; h < kHeads; ++h) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(lg[h], a2[h], c2v[h]));
+          lsum[h] += p;
+          xs[h] = product_digits(p, 536870912.f);
+        }
+        __builtin_amdgcn_wave_barrier();
+        *reinterpret_cast<v4i*>(lbytes + (size_t)jt * 4 + x_wr) = xs;
+#pragma unroll
+        for (int e = 0; e < BITS; ++e)
+          *reinterpret_cast<v4i*>(stage + (BITS == 1 ? buf * 1024 : 0) + lane * (16 * BITS) + 16 * e) =
+              cg[slot][e];
+      };
+      v4i acc_w = {0, 0, 0, 0};
+      const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+      auto m_step = [&](int k, int d) {
+        const int buf = d & 1;
+        const int jt = tile_start(k);
+        const uint8_t* xr = lbytes + (size_t)jt * 4 + x_rd;
+        const uint8_t* vr = stage + (BITS == 1 ? buf * 1024 : 0) + v_rd;
+        const v2i a_lo = lds_read_tr8(xr), a_hi = lds_read_tr8(xr + 128);
+        const v4i A = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+        v4i raw[BITS];
+#pragma unroll
+        for (int cb = 0; cb < BITS; ++cb) {
+          const v2i b_lo = lds_read_tr8(vr + 16 * cb), b_hi = lds_read_tr8(vr + 16 * cb + 128 * BITS);
+          raw[cb] = (v4i){b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+        }
+        const int nslot = (d + 1) % kRingV;
+        if (k + 1 < n_my) prep_tile(nslot, k + 1, buf ^ 1);
+        pin_order();
+        load_tile(nslot, k + 1 + kRingV);
+        pin_order();
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          v4i B;
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            B[v] = BITS == 1 ? operand_variant<1>((uint32_t)raw[0][v], p)
+                             : operand_variant<2>((uint32_t)raw[p >> 2][v], p & 3);
+          acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B, acc[p], 0, 0, 0);
+        }
+        acc_w = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, ones, acc_w, 0, 0, 0);
+        if ((k & (tpg - 1)) == tpg - 1) {       // last tile of a value group: fold it into fp32
+          const float wsum = digits_to_float(acc_w);
+          acc_w = (v4i){0, 0, 0, 0};
+#pragma unroll
+          for (int p = 0; p < 8; ++p) {
+            // accumulator p holds channel c_lo + 7 - p (b = 1), c_lo + 3 - p or c_hi + 3 - (p - 4)
+            const int i = 7 - p;
+            const int vec = BITS == 1 ? i >> 2 : p >> 2, el = BITS == 1 ? i & 3 : 3 - (p & 3);
+            const uint32_t mpair = (uint32_t)gmn[vec][el >> 1];
+            const float mn = __half2float(__ushort_as_half((uint16_t)((el & 1) ? mpair >> 16 : mpair & 0xffffu)));
+            // the operand byte of a set code is 2^p (b = 1) resp. code * {1, 4, 16, 16}: take that out
+            const float sc = gsc[vec][el] * variant_weight<BITS>(BITS == 1 ? p : (p & 3));
+            facc[p] = fmaf(digits_to_float(acc[p]), sc, fmaf(wsum, mn, facc[p]));
+            acc[p] = (v4i){0, 0, 0, 0};
+          }
+          pin_order();
+          load_group((k >> tsh) + 1);
+          pin_order();
+        }
+        lds_publish();
+      };
+      if (n_my > 0) {
+#pragma unroll
+        for (int d = 0; d < kRingV; ++d) load_tile(d, d);
+        load_group(0);
+        prep_tile(0, 0, 0);
+        lds_publish();
+        load_tile(0, kRingV);
+        pin_order();
+        for (int k = 0; k < n_my; k += kRingV) {
+#pragma unroll
+          for (int d = 0; d < kRingV; ++d)
+            if (k + d < n_my) m_step(k + d, d);
+        }
+      }
+      Fv = 0;
+    } }
+    if constexpr (!VCH) { if (nv > 0) {
       // Pipeline over 64-token tiles (tile k of this wave starts at token (wave + 8k) * 64):
       //   G(k)  global loads of the tile's codes, scale and min into a ring of registers
       //   P(k)  weights p = 2^(a2*s + c2) from the logits in LDS, their fixed-point digits X(k)
@@ -656,7 +786,7 @@ fused_row_kernel(const FusedArgs a) {
       for (int d = 0; d < kRingV; ++d)                            // the wave's last 1..kRingV tiles
         if (j0 + d * step < nv) m_step(j0 + d * step, d, false);
       Fv = F_acc;
-    }
+    } }
     CQ_CLK(4);
     CQ_CLKW(48);
   } else {
@@ -739,7 +869,8 @@ fused_row_kernel(const FusedArgs a) {
       // column n16 of accumulator p is code byte n16 (b = 1) or 16 * (p / 4) + n16 (b = 2)
       const int ch = BITS == 1 ? 32 * (n16 >> 2) + 31 - 8 * (n16 & 3) - p
                                : 64 * (p >> 2) + 16 * (n16 >> 2) + 15 - 4 * (n16 & 3) - (p & 3);
-      partial[kb * kD + ch] = v * variant_weight<BITS>(BITS == 1 ? p : (p & 3));
+      // channel-wise values are accumulated in units of 2^-29 (the weights' fixed point)
+      partial[kb * kD + ch] = VCH ? v * 0x1p-29f : v * variant_weight<BITS>(BITS == 1 ? p : (p & 3));
     }
   } else if (kb == 0) {
 #pragma unroll
@@ -825,9 +956,17 @@ long long device_cu_count() {
   return n_cus;
 }
 
+// Chunks of a split row start at multiples of `unit` key groups: whole 64-token value tiles and,
+// with channel-wise values, whole value groups.
+int chunk_unit(const DecodeShape& s) {
+  int align = 64;
+  if (s.v_axis == CQ_AXIS_CHANNEL && s.v_group > align) align = s.v_group;
+  return align / s.k_group > 1 ? align / s.k_group : 1;
+}
+
 // largest chunk of a row split into n_chunks (same arithmetic as the kernel)
 void chunk_extent(const DecodeShape& s, int n_chunks, int* nv_max, int* nt_max) {
-  const int unit = 64 / s.k_group > 1 ? 64 / s.k_group : 1;
+  const int unit = chunk_unit(s);
   const int n_units = s.n_vis / (s.k_group * unit);
   const int n_tblocks = (s.n_text + 63) / 64;
   *nv_max = 0;
@@ -848,12 +987,14 @@ void chunk_extent(const DecodeShape& s, int n_chunks, int* nv_max, int* nt_max) 
 FusedPlan make_plan(const DecodeShape& s, size_t workspace_bytes) {
   FusedPlan p;
   if (s.d != kD || (s.bits != 1 && s.bits != 2)) return p;
-  if (s.k_axis != CQ_AXIS_CHANNEL || s.v_axis != CQ_AXIS_TOKEN || s.v_group != kD) return p;
+  if (s.k_axis != CQ_AXIS_CHANNEL) return p;
+  if (s.v_axis == CQ_AXIS_TOKEN ? s.v_group != kD : (s.v_group != 64 && s.v_group != 128)) return p;
   if (s.k_group != 32 && s.k_group != 64 && s.k_group != 128) return p;
   if (s.g > 2 * kHeads || s.n_vis % 64 != 0) return p;
+  if (s.v_axis == CQ_AXIS_CHANNEL && s.n_vis % s.v_group != 0) return p;
   p.nhb = (s.g + kHeads - 1) / kHeads;
   const long long rows = (long long)s.B * s.Hkv * p.nhb;
-  const int unit = 64 / s.k_group > 1 ? 64 / s.k_group : 1;
+  const int unit = chunk_unit(s);
   const int n_units = s.n_vis / (s.k_group * unit);
   const int max_chunks = n_units < 64 ? (n_units > 0 ? n_units : 1) : 64;
   // Fewest chunks that fit LDS.  Splitting a row that fits only to fill idle CUs does not pay:
@@ -933,6 +1074,7 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
   a.out = static_cast<__half*>(out);
   a.Hq = s.Hq; a.Hkv = s.Hkv; a.g = s.g; a.n_vis = s.n_vis; a.n_text = s.n_text;
   a.n_text_cap = s.n_text_cap; a.k_group = s.k_group;
+  a.v_group = s.v_group; a.unit = chunk_unit(s);
   a.calib_mode = calib.mode; a.tau1 = calib.tau1; a.tau2 = calib.tau2;
   a.gamma = calib.gamma; a.delta = calib.delta; a.softmax_scale = softmax_scale;
   a.stride = plan.stride;
@@ -945,16 +1087,23 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
 #endif
   void (*kern)(const FusedArgs) = nullptr;
   int slot = 0;
-  switch (s.k_group * 4 + s.bits) {
-    case 32 * 4 + 1: kern = fused_row_kernel<2, 1>; slot = 0; break;
-    case 64 * 4 + 1: kern = fused_row_kernel<4, 1>; slot = 1; break;
-    case 128 * 4 + 1: kern = fused_row_kernel<8, 1>; slot = 2; break;
-    case 32 * 4 + 2: kern = fused_row_kernel<2, 2>; slot = 3; break;
-    case 64 * 4 + 2: kern = fused_row_kernel<4, 2>; slot = 4; break;
-    case 128 * 4 + 2: kern = fused_row_kernel<8, 2>; slot = 5; break;
+  const bool vch = s.v_axis == CQ_AXIS_CHANNEL;
+  switch ((s.k_group * 4 + s.bits) * 2 + (vch ? 1 : 0)) {
+    case (32 * 4 + 1) * 2: kern = fused_row_kernel<2, 1, false>; slot = 0; break;
+    case (64 * 4 + 1) * 2: kern = fused_row_kernel<4, 1, false>; slot = 1; break;
+    case (128 * 4 + 1) * 2: kern = fused_row_kernel<8, 1, false>; slot = 2; break;
+    case (32 * 4 + 2) * 2: kern = fused_row_kernel<2, 2, false>; slot = 3; break;
+    case (64 * 4 + 2) * 2: kern = fused_row_kernel<4, 2, false>; slot = 4; break;
+    case (128 * 4 + 2) * 2: kern = fused_row_kernel<8, 2, false>; slot = 5; break;
+    case (32 * 4 + 1) * 2 + 1: kern = fused_row_kernel<2, 1, true>; slot = 6; break;
+    case (64 * 4 + 1) * 2 + 1: kern = fused_row_kernel<4, 1, true>; slot = 7; break;
+    case (128 * 4 + 1) * 2 + 1: kern = fused_row_kernel<8, 1, true>; slot = 8; break;
+    case (32 * 4 + 2) * 2 + 1: kern = fused_row_kernel<2, 2, true>; slot = 9; break;
+    case (64 * 4 + 2) * 2 + 1: kern = fused_row_kernel<4, 2, true>; slot = 10; break;
+    case (128 * 4 + 2) * 2 + 1: kern = fused_row_kernel<8, 2, true>; slot = 11; break;
     default: return hipErrorInvalidValue;
   }
-  static size_t configured[6] = {0, 0, 0, 0, 0, 0};
+  static size_t configured[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if (plan.lds > configured[slot]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan.lds);

@@ -239,3 +239,55 @@ def test_split_rows_agree_with_whole_rows(kernel_path, chunks, monkeypatch):
             c.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
     finally:
         cq.cq_set_kernel_path(prev)
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("kg,vg", [(128, 128), (128, 64), (64, 128), (32, 64), (32, 128)])
+def test_tuned_channelwise_values(kernel_path, bits, kg, vg):
+    """Paper-literal value quantization (channel-wise over groups of tokens, Sec. 3.1) on the
+    tuned kernels: whole rows, every calibration mode, g = 4 and g = 6."""
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    cases = []
+    for w in (synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=2304, n_text=200),
+              synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=1280, n_text=70)):
+        cases.append(Case(w, H.layout_of(w, bits, kg, vg, 0, 0)))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        for c in cases:
+            c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+            c.check(cq.CQ_CALIB_NONE)
+            c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, n_text=0)
+    finally:
+        cq.cq_set_kernel_path(prev)
+
+
+@pytest.mark.parametrize("chunks", [2, 3])
+def test_tuned_channelwise_values_on_split_rows(kernel_path, chunks, monkeypatch):
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
+    cases = []
+    for kg, vg in ((128, 128), (32, 128), (64, 64)):
+        w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200)
+        cases.append(Case(w, H.layout_of(w, 1, kg, vg, 0, 0)))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        for c in cases:
+            c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+            c.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
+    finally:
+        cq.cq_set_kernel_path(prev)
+
+
+def test_full_length_row_with_channelwise_values(kernel_path):
+    """configs[2]-length rows (8192 + 512 tokens) with channel-wise values, tuned kernels."""
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    w = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8)
+    c = Case(w, H.layout_of(w, 1, 128, 128, 0, 0))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    finally:
+        cq.cq_set_kernel_path(prev)
