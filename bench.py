@@ -52,6 +52,7 @@ def main() -> int:
                          "groups of tokens (the paper's own choice)")
     ap.add_argument("--path", choices=["auto", "generic", "tuned"], default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fp16-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="override the batch (debugging only)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -198,6 +199,56 @@ def main() -> int:
             reads.append(e0.elapsed_time(e1))
     reads.sort()
     stream_ms = reads[len(reads) // 2]
+    # ---- 16-bit baseline in the same harness (the paper's "16-bit baseline", Sec. 4.4): the same
+    # call with the whole cache left in fp16, i.e. no visual tokens and every token in the fp16
+    # tail.  Same kernel family, same launch path, nothing quantized.
+    fp16_baseline = None
+    if not args.no_fp16_baseline:
+        n_all = w.n_vis + w.n_text
+        lay16 = cq.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, 0, args.bits,
+                               cq.CQ_AXIS_CHANNEL, cq.CQ_AXIS_TOKEN, args.group, args.group)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(w.seed + 17)
+        shape16 = (w.batch, w.n_kv_heads, n_all, w.head_dim)
+        sets16 = [(torch.randn(shape16, generator=gen, device=dev, dtype=torch.float16),
+                   torch.randn(shape16, generator=gen, device=dev, dtype=torch.float16))
+                  for _ in range(2)]
+        ws16 = torch.empty(cq.cq_decode_workspace_bytes(lay16, n_all), dtype=torch.uint8, device=dev)
+        none = cq.make_calib(cq.CQ_CALIB_NONE)
+
+        def step16(i):
+            k16, v16 = sets16[i % 2]
+            cq.cq_decode_attn(lay16, sets[0]["q"], None, None, k16, v16, n_all, none, 0.0,
+                              sets[0]["out"], ws16)
+
+        prev_path = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+        try:
+            step16(0)
+            torch.cuda.synchronize()
+            kernel16 = "fused_row_kernel, text path only (one launch)"
+        except cq.CqError:
+            cq.cq_set_kernel_path(cq.CQ_PATH_AUTO)
+            kernel16 = "shape-agnostic kernels (the row does not fit the tuned kernel's LDS)"
+        n16 = 20 if kernel16.startswith("fused") else 3
+        for i in range(2):
+            step16(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n16):
+            step16(i)
+        e1.record()
+        torch.cuda.synchronize()
+        cq.cq_set_kernel_path(prev_path)
+        ms16 = e0.elapsed_time(e1) / n16
+        bytes16 = w.batch * w.n_kv_heads * n_all * per_text + 2 * w.batch * w.n_q_heads * w.head_dim * 2
+        fp16_baseline = {"ms": ms16, "kernel": kernel16, "bytes_per_call": bytes16,
+                         "GB/s": bytes16 / (ms16 * 1e-3) / 1e9,
+                         "frac_of_hbm_peak": bytes16 / (ms16 * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "speedup_of_quantized_cache": ms16 / mean_ms,
+                         "cache_bytes_ratio": bytes16 / bytes_call}
+        del sets16, ws16
+
     # one plain copy of known size: the launch that byte counters (FETCH_SIZE / WRITE_SIZE) are
     # scaled with when this command runs under rocprofv3 --pmc
     cq.cq_bench_stream_copy(probe[nb:], probe, nb)
@@ -263,6 +314,7 @@ def main() -> int:
                                                 "decode_vs_stream_read": stream_ms / mean_ms},
                      "bytes_per_visual_token_per_kv_head": per_vis,
                      "bytes_per_text_token_per_kv_head": per_text},
+        "fp16_baseline": fp16_baseline,
         "quantizer": {"ms": q_ms, "bytes_read_plus_written": q_bytes,
                       "GB/s": q_bytes / (q_ms * 1e-3) / 1e9,
                       "frac_of_hbm_peak": q_bytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
