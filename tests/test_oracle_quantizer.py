@@ -228,3 +228,34 @@ def test_axis_semantics_by_hand():
     # the larger of the two tokens gets code 1 (when they differ)
     bigger0 = x[0, 0, 0] > x[0, 0, 1]
     assert np.array_equal(qc["codes"][0, 0, 0].astype(bool), bigger0)
+
+
+# --------------------------------------------------------------------------- golden fixtures
+def _golden_lines(name):
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    for line in open(path):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            yield [part.split() for part in line.split("|")]
+
+
+def test_golden_packing_examples_worked_by_hand():
+    n = 0
+    for (N, M), codes, (word,) in _golden_lines("packing_appendix_examples.txt"):
+        N, M, codes, word = int(N), int(M), [int(c) for c in codes], int(word)
+        assert len(codes) == M // N
+        assert int(O.pack(codes, N, M)[0]) == word
+        assert [int(c) for c in O.unpack(np.array([word], dtype=np.uint64), N, M)[:len(codes)]] == codes
+        n += 1
+    assert n >= 10
+
+
+def test_golden_quantize_examples_worked_by_hand():
+    n = 0
+    for (b,), values, codes in _golden_lines("quantize_equation_examples.txt"):
+        x = np.array([float(v) for v in values], dtype=np.float64)
+        got = O.discretize(x, x.min(), x.max(), int(b))
+        assert [int(c) for c in np.asarray(got).ravel()] == [int(c) for c in codes], (b, values)
+        n += 1
+    assert n >= 6
