@@ -108,9 +108,18 @@ __device__ inline float wave_max(float v) {
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
   return v;
 }
+template <int CTRL> __device__ inline float dpp_f32(float v);
+// Sum over the wave on the DPP network; the result is wave-uniform.
 __device__ inline float wave_sum(float v) {
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
+  v += dpp_f32<0xB1>(v);      // quad_perm 1,0,3,2
+  v += dpp_f32<0x4E>(v);      // quad_perm 2,3,0,1: every lane holds its quad's sum
+  v += dpp_f32<0x141>(v);     // row_half_mirror: the other quad of the half row
+  v += dpp_f32<0x140>(v);     // row_mirror: the other half row
+  const int r1 = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false);
+  v += __builtin_bit_cast(float, r1);     // row_bcast15: rows 1, 3 add the row before them
+  const int r2 = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false);
+  v += __builtin_bit_cast(float, r2);     // row_bcast31: rows 2, 3 add rows 0 + 1
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 // Maximum over the wave of a non-negative float, on the DPP network (no LDS round trips); the
 // result is wave-uniform.  Non-negative floats order like their bit patterns.
@@ -185,9 +194,11 @@ __device__ inline int fixed_point_shift(float bound) {
   frexpf(bound, &e);           // bound = m * 2^e, m in [0.5, 1)
   return max(-90, min(90, 29 - e));
 }
-// the four signed base-256 digits of trunc(a * b), as the four bytes of the result
+// the four signed base-256 digits of a * b (truncated), as the four bytes of the result:
+// digits(x) = (x + 0x00808080) ^ 0x00808080, with the addition riding on the fma (the float sum is
+// exact to one unit below 2^24 and to fp32 precision above, which is all the product has)
 __device__ inline int product_digits(float a, float b) {
-  return ((int)(a * b) + 0x00808080) ^ 0x00808080;
+  return (int)fmaf(a, b, 8421504.f) ^ 0x00808080;
 }
 
 extern __shared__ __align__(16) uint8_t smem[];
@@ -683,6 +694,7 @@ fused_row_kernel(const FusedArgs a) {
       // running fixed-point shift: set by the largest value scale met so far; when a tile lowers
       // it, the integer accumulators are banked into fp32 before that tile is added
       int F_prep = 90, F_acc = 90, F_tile[2] = {90, 90};
+      float fit_below = ldexpf(1.f, 29 - 90);   // scales below this fit the shift F_prep
       const uint32_t* vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS);
       const int step = kVisWaves * 64;
       const int last = nv - 64;                // first token of the row's last tile
@@ -701,7 +713,11 @@ fused_row_kernel(const FusedArgs a) {
         vmr[slot] = vm_row[j];
       };
       auto prep_tile = [&](int slot, int jt, int buf) {
-        F_prep = min(F_prep, fixed_point_shift(wave_max_nonneg(vsr[slot])));
+        if (__builtin_amdgcn_ballot_w64(vsr[slot] >= fit_below) != 0) {
+          // some token's scale does not fit the running shift (rare after the first tiles)
+          F_prep = min(F_prep, fixed_point_shift(wave_max_nonneg(vsr[slot])));
+          fit_below = ldexpf(1.f, 29 - F_prep);
+        }
         F_tile[buf] = F_prep;
         const float vsf = ldexpf(vsr[slot], F_prep);
         const float vmf = __half2float(__ushort_as_half(vmr[slot]));
