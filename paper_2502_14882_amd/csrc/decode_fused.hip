@@ -371,9 +371,9 @@ fused_row_kernel(const FusedArgs a) {
         const v4i A1 = {r10[0], r10[1], r11[0], r11[1]};
         const float bias_h = group_bias(qv0, qv1, m0[slot], m1[slot], inv_w, lane);
         __builtin_amdgcn_wave_barrier();   // operand rows are consumed before logits land there
-#pragma unroll
-        for (int tile = 0; tile < TILES; ++tile) {
-          v4i B0, B1;
+        // the operands of tile + 1 are formed before the products of this tile are issued, so no
+        // product waits on the ANDs right in front of it
+        auto expand = [&](int tile, v4i& B0, v4i& B1) {
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
             if constexpr (BITS == 1) {
@@ -384,6 +384,14 @@ fused_row_kernel(const FusedArgs a) {
               B1[v] = operand_variant<2>(w[slot][tile][1], v);
             }
           }
+        };
+        v4i B0n, B1n;
+        expand(0, B0n, B1n);
+#pragma unroll
+        for (int tile = 0; tile < TILES; ++tile) {
+          const v4i B0 = B0n, B1 = B1n;
+          if (tile + 1 < TILES) expand(tile + 1, B0n, B1n);
+          __builtin_amdgcn_sched_barrier(0);
           v4i c = {0, 0, 0, 0};
           c = __builtin_amdgcn_mfma_i32_16x16x64_i8(A0, B0, c, 0, 0, 0);
           c = __builtin_amdgcn_mfma_i32_16x16x64_i8(A1, B1, c, 0, 0, 0);
@@ -635,13 +643,20 @@ fused_row_kernel(const FusedArgs a) {
         pin_order();
         load_tile(nslot, k + 1 + kRingV);
         pin_order();
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
+        auto variant_of = [&](int p) {
           v4i B;
 #pragma unroll
           for (int v = 0; v < 4; ++v)
             B[v] = BITS == 1 ? operand_variant<1>((uint32_t)raw[0][v], p)
                              : operand_variant<2>((uint32_t)raw[p >> 2][v], p & 3);
+          return B;
+        };
+        v4i Bn = variant_of(0);
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {       // operand p + 1 is formed before product p is issued
+          const v4i B = Bn;
+          if (p < 7) Bn = variant_of(p + 1);
+          __builtin_amdgcn_sched_barrier(0);
           acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B, acc[p], 0, 0, 0);
         }
         acc_w = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, ones, acc_w, 0, 0, 0);
@@ -782,13 +797,22 @@ fused_row_kernel(const FusedArgs a) {
           }
           F_acc = F_tile[buf];
         }
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {       // p = mask variant (b = 1) or 4 * block + variant
+        // p = mask variant (b = 1) or 4 * block + variant; the operand of product p + 1 is formed
+        // before product p is issued, so no product waits on the ANDs right in front of it
+        auto variant_of = [&](int p) {
           v4i B;
 #pragma unroll
           for (int v = 0; v < 4; ++v)
             B[v] = BITS == 1 ? operand_variant<1>((uint32_t)raw[0][v], p)
                              : operand_variant<2>((uint32_t)raw[p >> 2][v], p & 3);
+          return B;
+        };
+        v4i Bn = variant_of(0);
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          const v4i B = Bn;
+          if (p < 7) Bn = variant_of(p + 1);
+          __builtin_amdgcn_sched_barrier(0);
           acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B, acc[p], 0, 0, 0);
         }
         lds_publish();
