@@ -385,16 +385,7 @@ fused_row_kernel(const FusedArgs a) {
             }
           }
         };
-        v4i B0n, B1n;
-        expand(0, B0n, B1n);
-#pragma unroll
-        for (int tile = 0; tile < TILES; ++tile) {
-          const v4i B0 = B0n, B1 = B1n;
-          if (tile + 1 < TILES) expand(tile + 1, B0n, B1n);
-          __builtin_amdgcn_sched_barrier(0);
-          v4i c = {0, 0, 0, 0};
-          c = __builtin_amdgcn_mfma_i32_16x16x64_i8(A0, B0, c, 0, 0, 0);
-          c = __builtin_amdgcn_mfma_i32_16x16x64_i8(A1, B1, c, 0, 0, 0);
+        auto finish_tile = [&](int tile, const v4i& c) {
           const int lo = c[0] + (c[1] << 8), hi = c[2] + (c[3] << 8);
           const float sv = fmaf((float)hi, inv_f16, fmaf((float)lo, inv_f, bias_h));
           // lanes of unused heads (hres >= g) see q = 0, finish with sv = 0 and write their own
@@ -402,6 +393,24 @@ fused_row_kernel(const FusedArgs a) {
           lrow[(t * TILES + tile) * 16] = sv;
           mn = fminf(mn, sv);
           mx = fmaxf(mx, sv);
+        };
+        // two tiles at a time: their four products are interleaved so that the second product of
+        // a tile (which accumulates onto the first) does not wait for it
+        static_assert(TILES % 2 == 0, "tiles are taken in pairs");
+#pragma unroll
+        for (int tile = 0; tile < TILES; tile += 2) {
+          v4i Ba0, Ba1, Bb0, Bb1;
+          expand(tile, Ba0, Ba1);
+          expand(tile + 1, Bb0, Bb1);
+          __builtin_amdgcn_sched_barrier(0);
+          v4i ca = {0, 0, 0, 0}, cb = {0, 0, 0, 0};
+          ca = __builtin_amdgcn_mfma_i32_16x16x64_i8(A0, Ba0, ca, 0, 0, 0);
+          cb = __builtin_amdgcn_mfma_i32_16x16x64_i8(A0, Bb0, cb, 0, 0, 0);
+          ca = __builtin_amdgcn_mfma_i32_16x16x64_i8(A1, Ba1, ca, 0, 0, 0);
+          cb = __builtin_amdgcn_mfma_i32_16x16x64_i8(A1, Bb1, cb, 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          finish_tile(tile, ca);
+          finish_tile(tile + 1, cb);
         }
       };
 #pragma unroll
