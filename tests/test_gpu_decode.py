@@ -291,3 +291,47 @@ def test_full_length_row_with_channelwise_values(kernel_path):
         c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
     finally:
         cq.cq_set_kernel_path(prev)
+
+
+@pytest.mark.parametrize("chunks", [1, 3])
+def test_decode_replayed_from_a_hip_graph(kernel_path, chunks, monkeypatch):
+    """cq_decode_attn allocates nothing and blocks on nothing, so a serving loop can record it
+    into a HIP graph: every replay, with eager work and synchronisations in between, must
+    reproduce the eager result bit for bit (whole rows and split rows)."""
+    if kernel_path != "auto":
+        pytest.skip("runs once")
+    monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200)
+    c = Case(w, H.layout_of(w))
+    calib = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    ws = torch.empty(cq.cq_decode_workspace_bytes(c.lay, w.n_text), dtype=torch.uint8, device="cuda")
+    qs = [c.x["q"], (c.x["q"] * 0.5).contiguous(), (-c.x["q"]).contiguous()]
+    eager = []
+    for q in qs:
+        out = torch.empty_like(q)
+        cq.cq_decode_attn(c.lay, q, c.k_dev, c.v_dev, c.x["k_text"], c.x["v_text"], w.n_text, calib,
+                          0.0, out, ws)
+        torch.cuda.synchronize()
+        eager.append(out.clone())
+    outs = [torch.empty_like(q) for q in qs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):       # warm-up on the capture stream, as torch asks for
+        cq.cq_decode_attn(c.lay, qs[0], c.k_dev, c.v_dev, c.x["k_text"], c.x["v_text"], w.n_text,
+                          calib, 0.0, outs[0], ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for q, out in zip(qs, outs):
+            cq.cq_decode_attn(c.lay, q, c.k_dev, c.v_dev, c.x["k_text"], c.x["v_text"], w.n_text,
+                              calib, 0.0, out, ws)
+    for rep in range(3):
+        for out in outs:
+            out.zero_()
+        ws.zero_()                      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(outs, eager):
+            assert torch.equal(got, want), "replay %d differs from the eager result" % rep
