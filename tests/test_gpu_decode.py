@@ -335,3 +335,36 @@ def test_decode_replayed_from_a_hip_graph(kernel_path, chunks, monkeypatch):
         torch.cuda.synchronize()
         for got, want in zip(outs, eager):
             assert torch.equal(got, want), "replay %d differs from the eager result" % rep
+
+
+@pytest.mark.parametrize("bits", [1, 2])
+def test_full_size_long_context_config_on_sampled_rows(kernel_path, bits):
+    """configs[4] at full size (batch 8, g = 6, 65536 + 1024 tokens) through the launches bench.py
+    times (rows split into chunks, two head blocks, extrema + partial + combine); the oracle
+    checks sampled (batch, KV head) rows, each one independently."""
+    if kernel_path != "auto":
+        pytest.skip("full size runs on the tuned kernels only")
+    w = synth.WORKLOADS[4]
+    lay = H.layout_of(w, bits)
+    x = synth.make_inputs(w, "cuda")
+    k_dev, v_dev = cq.cq_quantize_kv(lay, x["k"], x["v"])
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        out = cq.cq_decode_attn(lay, x["q"], k_dev, v_dev, x["k_text"], x["v_text"], w.n_text,
+                                cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0))
+        torch.cuda.synchronize()
+    finally:
+        cq.cq_set_kernel_path(prev)
+    g = w.n_q_heads // w.n_kv_heads
+    for b, h in ((0, 0), (w.batch - 1, w.n_kv_heads - 1), (3, 5)):
+        kq = O.quantize_tensor(x["k"][b:b + 1, h:h + 1].cpu().numpy(), bits, O.AXIS_CHANNEL, 128)
+        vq = O.quantize_tensor(x["v"][b:b + 1, h:h + 1].cpu().numpy(), bits, O.AXIS_TOKEN, 128)
+        assert np.array_equal(H.words_of(k_dev.codes[b:b + 1, h:h + 1]), kq["words"])
+        assert np.array_equal(H.words_of(v_dev.codes[b:b + 1, h:h + 1]), vq["words"])
+        ref = O.decode_attn(x["q"][b:b + 1, h * g:(h + 1) * g].cpu().numpy(), kq, vq,
+                            x["k_text"][b:b + 1, h:h + 1].cpu().numpy(),
+                            x["v_text"][b:b + 1, h:h + 1].cpu().numpy(), w.n_text,
+                            O.CALIB_DYNAMIC, 1.0, 2.0)
+        got = out[b:b + 1, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)
+        err = O.rel_l2(got, ref)
+        assert err <= H.REL_L2_TOL, "row (%d,%d): rel L2 %.3e" % (b, h, err)

@@ -137,3 +137,32 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path, bits, group):
         _run(w, H.layout_of(w, bits, group, group), x, what="tuned b=%d G=%d" % (bits, group))
     finally:
         cq.cq_set_kernel_path(prev)
+
+
+@pytest.mark.parametrize("bits,group", [(1, 128), (2, 32)])
+def test_full_size_quantizer_config_on_sampled_rows(kernel_path, bits, group):
+    """configs[3] at full size (batch 128, 8 KV heads, 16384 tokens), drawn on the GPU as
+    bench.py does and quantized by the launch bench.py times; the oracle checks sampled
+    (batch, KV head) rows bit for bit, each one independently (rows do not interact)."""
+    if kernel_path != "auto":
+        pytest.skip("full size runs on the tuned kernels only")
+    from oracle import cq_oracle as O
+    w = synth.WORKLOADS[3]
+    lay = H.layout_of(w, bits, group, group)
+    x = synth.make_inputs(w, "cuda", parts=("k", "v"))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        k_out, v_out = cq.cq_quantize_kv(lay, x["k"], x["v"])
+        torch.cuda.synchronize()
+    finally:
+        cq.cq_set_kernel_path(prev)
+    rng = np.random.default_rng(11)
+    rows = {(0, 0), (w.batch - 1, w.n_kv_heads - 1)}
+    while len(rows) < 5:
+        rows.add((int(rng.integers(w.batch)), int(rng.integers(w.n_kv_heads))))
+    for b, h in sorted(rows):
+        for name, out, axis in (("k", k_out, lay.k_axis), ("v", v_out, lay.v_axis)):
+            ref = O.quantize_tensor(x[name][b:b + 1, h:h + 1].cpu().numpy(), bits, axis, group)
+            got = cq.QTensor(out.codes[b:b + 1, h:h + 1], out.scale[b:b + 1, h:h + 1],
+                             out.min[b:b + 1, h:h + 1])
+            H.assert_qtensor_equal(got, ref, "configs[3] %s row (%d,%d)" % (name, b, h))
