@@ -131,12 +131,15 @@ def main() -> int:
                          "kernel": "quantize_tile_kernel (keys + values launches)"},
             "sweep": sweep}))
         return 0
+    # --group is the key group (tokens); token-wise values keep one group per token, channel-wise
+    # values use the same token group as the keys
+    v_group = args.group if args.v_axis == "channel" else w.head_dim
     lay = cq.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_vis, args.bits,
                          cq.CQ_AXIS_CHANNEL,
                          cq.CQ_AXIS_CHANNEL if args.v_axis == "channel" else cq.CQ_AXIS_TOKEN,
-                         args.group, args.group)
+                         args.group, v_group)
     calib = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
-    bytes_call, per_vis, per_text = algorithmic_bytes(w, args.bits, args.group, args.group)
+    bytes_call, per_vis, per_text = algorithmic_bytes(w, args.bits, args.group, v_group)
 
     # ---- resident inputs: several independent sets so that no call finds its cache warm
     n_sets = int(min(32, max(3, math.ceil(800e6 / bytes_call))))
@@ -333,7 +336,7 @@ def main() -> int:
         "config": {"workload": "configs[%d] %s" % (args.config, w.name), "batch": w.batch,
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_vis": w.n_vis, "n_text": w.n_text, "bits": args.bits,
-                   "k_group": args.group, "v_group": args.group, "v_axis": args.v_axis,
+                   "k_group": args.group, "v_group": v_group, "v_axis": args.v_axis,
                    "calib": "dynamic tau=(1,2)",
                    "kernel_path": args.path, "input_sets": n_sets},
         "launch": args.launch,
