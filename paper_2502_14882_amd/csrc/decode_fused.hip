@@ -24,6 +24,7 @@
 // compute-heavy visual phases.  Every stream keeps a ring of loads several tiles deep in flight.
 #include <hip/hip_fp16.h>
 
+#include <atomic>
 #include <cfloat>
 #include <cstdlib>
 
@@ -992,17 +993,21 @@ struct FusedPlan {
   size_t lds = 0, ws_minmax_floats = 0, ws_floats = 0;
 };
 
+constexpr int kMaxDevices = 64;
+
+// Compute units of the current device (cached per device; 256, the MI355X count, when there is
+// no device, as in host-only checks of the plan).
 long long device_cu_count() {
-  static int n_cus = 0;
-  if (n_cus == 0) {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      n_cus = v;
-    else
-      return 256;      // no device (host-only checks): the MI355X count
+  static std::atomic<int> n_cus[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  int v = n_cus[dev].load(std::memory_order_relaxed);
+  if (v == 0) {
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      return 256;
+    n_cus[dev].store(v, std::memory_order_relaxed);
   }
-  return n_cus;
+  return v;
 }
 
 // Chunks of a split row start at multiples of `unit` key groups: whole 64-token value tiles and,
@@ -1152,12 +1157,21 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
     case (128 * 4 + 2) * 2 + 1: kern = fused_row_kernel<8, 2, true>; slot = 11; break;
     default: return hipErrorInvalidValue;
   }
-  static size_t configured[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-  if (plan.lds > configured[slot]) {
+  // the kernel's dynamic LDS limit is raised once per (device, kernel) and only ever grows;
+  // concurrent callers may both raise it, which is harmless
+  static std::atomic<size_t> configured[kMaxDevices][12];
+  int dev = 0;
+  hipError_t de = hipGetDevice(&dev);
+  if (de != hipSuccess) return de;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (plan.lds > configured[dev][slot].load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)plan.lds);
     if (e != hipSuccess) return e;
-    configured[slot] = plan.lds;
+    size_t seen = configured[dev][slot].load(std::memory_order_relaxed);
+    while (seen < plan.lds &&
+           !configured[dev][slot].compare_exchange_weak(seen, plan.lds, std::memory_order_release)) {
+    }
   }
   const size_t pieces = (size_t)s.B * s.Hkv * plan.n_chunks;
   const size_t blocks = plan.nhb > 1 ? (pieces + 7) / 8 * 8 * plan.nhb : pieces;

@@ -1,4 +1,4 @@
-// Tuned quantizer for head_dim 128, b in {1, 2}, groups of 32/64/128 (gfx950).
+// Tuned quantizer for head_dim 128, b in {1, 2, 4, 8}, groups of 32/64/128 (gfx950).
 //
 // One 256-thread block quantizes a tile of 128 tokens x 128 channels (32 KB of fp16), read once
 // with 16-byte loads and kept in registers:
@@ -12,6 +12,9 @@
 //      fp16 x:  x > t_k  <=>  round-half-even((x-min)(2^b-1)/(max-min)) >= k   (Sec. 2.2 equation).
 //   3. codes by comparing packed halves against the thresholds (sign of t - x), bits gathered with
 //      v_perm + v_dot4, words assembled across adjacent lanes, MSB first as in the packing appendix.
+//   b in {4, 8} (too many thresholds): step 2 stores min and (2^b-1)/(max-min) per group, step 3
+//   evaluates the quantize equation per element in fp64 with that reciprocal and settles the
+//   rounding exactly (see exact_code); a lane's 8 channels fill one word (b = 4) or two (b = 8).
 // Results are bit-identical to evaluating the quantize equation element by element in fp64.
 #include <hip/hip_fp16.h>
 
@@ -84,6 +87,39 @@ __device__ inline uint32_t octet_codes(const v8h& x, const v8h* thr) {
   }
 }
 
+// round-half-even((x - alpha) L / D) for b in {4, 8}, from rinv = fl(L / D) (0 for a constant group).
+// x - alpha is exact in fp64; q = fl((x - alpha) * rinv) is within 2^-44 of the true quotient
+// (two roundings, q <= 255).  The true quotient is a ratio of integers with denominator
+// D / 2^-24 < 2^41, so it is either exactly k + 1/2 or at least 2^-42 away from it: a computed
+// fraction within 2^-43 of 1/2 is a tie (to even), anything else rounds by its computed fraction.
+__device__ inline uint32_t exact_code(_Float16 x, double alpha, double rinv) {
+  const double q = ((double)(float)x - alpha) * rinv;
+  const double f = floor(q);
+  const double frac = q - f;
+  uint32_t c = (uint32_t)(int)f;
+  if (fabs(frac - 0.5) < 0x1p-43) c += c & 1u;
+  else c += frac > 0.5 ? 1u : 0u;
+  return c;
+}
+
+// the 8 codes of one octet as packed words, first channel in the top bits (packing appendix)
+template <int BITS>
+__device__ inline void octet_words(const v8h& x, const double (&alpha)[8], const double (&rinv)[8],
+                                   uint32_t& w0, uint32_t& w1) {
+  uint32_t c[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) c[j] = exact_code(x[j], alpha[j], rinv[j]);
+  if constexpr (BITS == 4) {
+    w0 = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w0 |= c[j] << (28 - 4 * j);
+    w1 = 0;
+  } else {
+    w0 = (c[0] << 24) | (c[1] << 16) | (c[2] << 8) | c[3];
+    w1 = (c[4] << 24) | (c[5] << 16) | (c[6] << 8) | c[7];
+  }
+}
+
 struct QArgs {
   const __half* x;
   uint32_t* codes;
@@ -100,7 +136,10 @@ quantize_tile_kernel(const QArgs a) {
   constexpr int NG = AXIS == CQ_AXIS_CHANNEL ? kTile / GROUP : kD / GROUP;   // groups per tile / token
   __shared__ __align__(16) _Float16 s_part[2][4][kD];     // channel axis: per-wave min, max
   __shared__ __align__(16) _Float16 s_stat[kTile][4][2];  // token axis: min, max per (token, group)
-  __shared__ __align__(16) _Float16 s_thr[AXIS == CQ_AXIS_CHANNEL ? NG * L * kD : kTile * 4 * 4];
+  constexpr bool kWide = BITS > 2;                        // per-element arithmetic instead of thresholds
+  __shared__ __align__(16) _Float16 s_thr[kWide ? 8 : (AXIS == CQ_AXIS_CHANNEL ? NG * L * kD : kTile * 4 * 4)];
+  __shared__ __align__(16) double s_rinv[kWide ? (AXIS == CQ_AXIS_CHANNEL ? NG * kD : kTile * 4) : 1];
+  __shared__ __align__(16) _Float16 s_alpha[kWide ? (AXIS == CQ_AXIS_CHANNEL ? NG * kD : kTile * 4) : 8];
   __shared__ __align__(16) uint32_t s_codes[kTile * kWords];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -156,14 +195,39 @@ quantize_tile_kernel(const QArgs a) {
       const size_t meta = (tok0 / GROUP + g) * kD + c;
       a.scale[meta] = (float)(D / (double)L);
       a.minv[meta] = mbits;
+      if constexpr (kWide) {
+        s_alpha[g * kD + c] = __builtin_bit_cast(_Float16, mbits);
+        s_rinv[g * kD + c] = D > 0.0 ? (double)L / D : 0.0;
+      } else {
 #pragma unroll
-      for (int k = 1; k <= L; ++k)
-        s_thr[(g * L + (k - 1)) * kD + c] =
-            __builtin_bit_cast(_Float16, threshold_bits(alpha, D, k, L));
+        for (int k = 1; k <= L; ++k)
+          s_thr[(g * L + (k - 1)) * kD + c] =
+              __builtin_bit_cast(_Float16, threshold_bits(alpha, D, k, L));
+      }
     }
     __syncthreads();
     // ---- 3. codes
     const int g = (32 * wave) / GROUP;
+    if constexpr (kWide) {
+      double al[8], ri[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        al[j] = (double)(float)s_alpha[g * kD + c8 * 8 + j];
+        ri[j] = s_rinv[g * kD + c8 * 8 + j];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int tok = 32 * wave + 4 * i + ts;
+        uint32_t w0, w1;
+        octet_words<BITS>(x[i], al, ri, w0, w1);
+        if constexpr (BITS == 4) {
+          s_codes[tok * kWords + c8] = w0;
+        } else {
+          s_codes[tok * kWords + 2 * c8] = w0;
+          s_codes[tok * kWords + 2 * c8 + 1] = w1;
+        }
+      }
+    } else {
     v8h thr[L];
 #pragma unroll
     for (int k = 0; k < L; ++k) thr[k] = *reinterpret_cast<const v8h*>(&s_thr[(g * L + k) * kD + c8 * 8]);
@@ -181,6 +245,7 @@ quantize_tile_kernel(const QArgs a) {
         bits |= __shfl_xor(bits, 1);
         if ((c8 & 1) == 0) s_codes[tok * kWords + (c8 >> 1)] = bits;
       }
+    }
     }
   } else {
     // ---- 1. per-token extrema over the lanes of a channel group
@@ -218,9 +283,14 @@ quantize_tile_kernel(const QArgs a) {
       const size_t meta = (tok0 + tok) * NG + g;
       a.scale[meta] = (float)(D / (double)L);
       a.minv[meta] = mbits;
+      if constexpr (kWide) {
+        s_alpha[tok * 4 + g] = __builtin_bit_cast(_Float16, mbits);
+        s_rinv[tok * 4 + g] = D > 0.0 ? (double)L / D : 0.0;
+      } else {
 #pragma unroll
-      for (int k = 1; k <= L; ++k)
-        s_thr[(tok * 4 + g) * 4 + (k - 1)] = __builtin_bit_cast(_Float16, threshold_bits(alpha, D, k, L));
+        for (int k = 1; k <= L; ++k)
+          s_thr[(tok * 4 + g) * 4 + (k - 1)] = __builtin_bit_cast(_Float16, threshold_bits(alpha, D, k, L));
+      }
     }
     __syncthreads();
     // ---- 3. codes
@@ -228,6 +298,19 @@ quantize_tile_kernel(const QArgs a) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int tok = 32 * wave + 4 * i + ts;
+      if constexpr (kWide) {
+        const double a1 = (double)(float)s_alpha[tok * 4 + g], r1 = s_rinv[tok * 4 + g];
+        const double al[8] = {a1, a1, a1, a1, a1, a1, a1, a1}, ri[8] = {r1, r1, r1, r1, r1, r1, r1, r1};
+        uint32_t w0, w1;
+        octet_words<BITS>(x[i], al, ri, w0, w1);
+        if constexpr (BITS == 4) {
+          s_codes[tok * kWords + c8] = w0;
+        } else {
+          s_codes[tok * kWords + 2 * c8] = w0;
+          s_codes[tok * kWords + 2 * c8 + 1] = w1;
+        }
+        continue;
+      }
       v8h thr[L];
 #pragma unroll
       for (int k = 0; k < L; ++k) {
@@ -268,7 +351,7 @@ hipError_t launch_group(int group, const QArgs& a, unsigned blocks, hipStream_t 
 }  // namespace
 
 bool quantize_tuned_supported(int n_vis, int d, int bits, int axis, int group) {
-  if (d != kD || (bits != 1 && bits != 2)) return false;
+  if (d != kD || (bits != 1 && bits != 2 && bits != 4 && bits != 8)) return false;
   if (group != 32 && group != 64 && group != 128) return false;
   if (axis != CQ_AXIS_CHANNEL && axis != CQ_AXIS_TOKEN) return false;
   return n_vis > 0 && n_vis % kTile == 0;
@@ -279,11 +362,23 @@ hipError_t launch_quantize_tuned(const void* x_f16, const cq_qtensor_t& out, int
   const size_t blocks = (size_t)rows * (size_t)(n_vis / kTile);
   if (blocks > 0x7fffffffu) return hipErrorInvalidConfiguration;
   const QArgs a{static_cast<const __half*>(x_f16), out.codes, out.scale, out.min};
-  if (axis == CQ_AXIS_CHANNEL)
-    return bits == 1 ? launch_group<CQ_AXIS_CHANNEL, 1>(group, a, (unsigned)blocks, stream)
-                     : launch_group<CQ_AXIS_CHANNEL, 2>(group, a, (unsigned)blocks, stream);
-  return bits == 1 ? launch_group<CQ_AXIS_TOKEN, 1>(group, a, (unsigned)blocks, stream)
-                   : launch_group<CQ_AXIS_TOKEN, 2>(group, a, (unsigned)blocks, stream);
+  const unsigned nb = (unsigned)blocks;
+  if (axis == CQ_AXIS_CHANNEL) {
+    switch (bits) {
+      case 1: return launch_group<CQ_AXIS_CHANNEL, 1>(group, a, nb, stream);
+      case 2: return launch_group<CQ_AXIS_CHANNEL, 2>(group, a, nb, stream);
+      case 4: return launch_group<CQ_AXIS_CHANNEL, 4>(group, a, nb, stream);
+      case 8: return launch_group<CQ_AXIS_CHANNEL, 8>(group, a, nb, stream);
+    }
+  } else {
+    switch (bits) {
+      case 1: return launch_group<CQ_AXIS_TOKEN, 1>(group, a, nb, stream);
+      case 2: return launch_group<CQ_AXIS_TOKEN, 2>(group, a, nb, stream);
+      case 4: return launch_group<CQ_AXIS_TOKEN, 4>(group, a, nb, stream);
+      case 8: return launch_group<CQ_AXIS_TOKEN, 8>(group, a, nb, stream);
+    }
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace cq

@@ -117,7 +117,7 @@ def test_runs_on_a_side_stream():
     H.assert_qtensor_equal(v_out, vq, "side stream values")
 
 
-@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
 @pytest.mark.parametrize("group", [32, 64, 128])
 def test_tuned_path_takes_the_benchmark_layouts(kernel_path, bits, group):
     """head_dim 128, b in {1,2}, groups 32/64/128 must run on the tuned kernels (no silent
@@ -139,7 +139,7 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path, bits, group):
         cq.cq_set_kernel_path(prev)
 
 
-@pytest.mark.parametrize("bits,group", [(1, 128), (2, 32)])
+@pytest.mark.parametrize("bits,group", [(1, 128), (2, 32), (4, 64), (8, 128)])
 def test_full_size_quantizer_config_on_sampled_rows(kernel_path, bits, group):
     """configs[3] at full size (batch 128, 8 KV heads, 16384 tokens), drawn on the GPU as
     bench.py does and quantized by the launch bench.py times; the oracle checks sampled
@@ -166,3 +166,28 @@ def test_full_size_quantizer_config_on_sampled_rows(kernel_path, bits, group):
             got = cq.QTensor(out.codes[b:b + 1, h:h + 1], out.scale[b:b + 1, h:h + 1],
                              out.min[b:b + 1, h:h + 1])
             H.assert_qtensor_equal(got, ref, "configs[3] %s row (%d,%d)" % (name, b, h))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_wide_codes_round_exact_ties_to_even_on_the_tuned_path(kernel_path, bits):
+    """Every code boundary of a 4- or 8-bit grid hit exactly: values k + 1/2 steps of a group
+    whose range makes the step a power of two, on both axes."""
+    if kernel_path != "auto":
+        pytest.skip("runs once")
+    L = (1 << bits) - 1
+    w = synth.WORKLOADS[1].replace(batch=1, n_kv_heads=1, n_q_heads=1, n_vis=512)
+    x = synth.make_inputs(w, "cpu", parts=("k", "v"))
+    # group range [0, L/8] -> step 1/8: multiples of 1/16 are representable and odd ones are ties
+    grid = (torch.arange(0, 2 * L + 1, dtype=torch.float32) / 16.0).to(torch.float16)
+    ties = grid.repeat((512 + grid.numel() - 1) // grid.numel())[:512]
+    x["k"][0, 0, :, 7] = ties                       # channel 7 over the tokens
+    x["k"][0, 0, :, 8] = -ties
+    for t in range(0, 512, 37):
+        x["v"][0, 0, t, :] = ties[:128] if bits == 4 else ties[t % 64:t % 64 + 128]
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        for group in (32, 128):
+            _run(w, H.layout_of(w, bits, group, group), x, what="ties b=%d G=%d" % (bits, group))
+            _run(w, H.layout_of(w, bits, group, group, 1, 0), x, what="ties swapped b=%d" % bits)
+    finally:
+        cq.cq_set_kernel_path(prev)
