@@ -138,6 +138,17 @@ int cq_decode_attn(const cq_layout_t *layout, const void *q_f16, const cq_qtenso
                    float softmax_scale, void *out_f16, void *workspace,
                    size_t workspace_bytes, void *stream);
 
+/* Growth of the fp16 tail between decode steps (Sec. 3: only the visual tokens are quantized; the
+ * text tokens, including those generated while decoding, stay in 16 bits).  Copies the key and
+ * value of ONE new token per sequence, k_new_f16 / v_new_f16 [B, Hkv, 1, d] (device, fp16,
+ * 16-byte aligned), to position n_text of the tails k_text_f16 / v_text_f16
+ * [B, Hkv, n_text_cap, d] (device, owned by the caller).  The caller then decodes with n_text + 1.
+ * Errors: CQ_ERR_NULL, CQ_ERR_ALIGN, CQ_ERR_SHAPE (n_text < 0 or n_text >= n_text_cap),
+ * CQ_ERR_HIP.  Asynchronous on `stream`; allocates nothing. */
+int cq_append_text_kv(const cq_layout_t *layout, void *k_text_f16, void *v_text_f16,
+                      int32_t n_text, int32_t n_text_cap, const void *k_new_f16,
+                      const void *v_new_f16, void *stream);
+
 /* Kernel selection, for tests and comparisons.  AUTO picks the tuned kernels when the
  * shape allows and the generic ones otherwise; GENERIC forces the shape-agnostic
  * kernels; TUNED returns CQ_ERR_UNSUPPORTED instead of falling back.  Process-wide.

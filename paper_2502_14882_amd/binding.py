@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         L.cq_decode_attn.restype = ctypes.c_int
         L.cq_decode_attn.argtypes = [P(CqLayout), V, P(CqQTensor), P(CqQTensor), V, V, I, I,
                                      P(CqCalib), ctypes.c_float, V, V, ctypes.c_size_t, V]
+        L.cq_append_text_kv.restype = ctypes.c_int
+        L.cq_append_text_kv.argtypes = [P(CqLayout), V, V, I, I, V, V, V]
         L.cq_set_kernel_path.restype = ctypes.c_int
         L.cq_set_kernel_path.argtypes = [ctypes.c_int]
         L.cq_bench_stream_read.restype = ctypes.c_int
@@ -182,6 +184,18 @@ def cq_decode_attn(layout: CqLayout, q: torch.Tensor, k: Optional[QTensor], v: O
         ctypes.byref(calib) if calib is not None else None, float(softmax_scale),
         _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(q)))
     return out
+
+
+def cq_append_text_kv(layout: CqLayout, k_text: torch.Tensor, v_text: torch.Tensor, n_text: int,
+                      k_new: torch.Tensor, v_new: torch.Tensor) -> int:
+    """Write one new token per sequence, k_new / v_new [B, Hkv, 1, d], to slot n_text of the fp16
+    tails [B, Hkv, cap, d] (in place); returns the new n_text."""
+    for t in (k_text, v_text, k_new, v_new):
+        assert t.dtype == torch.float16 and t.is_contiguous()
+    assert k_text.shape == v_text.shape and k_new.shape == v_new.shape
+    _check(lib().cq_append_text_kv(ctypes.byref(layout), _ptr(k_text), _ptr(v_text), int(n_text),
+                                   int(k_text.shape[2]), _ptr(k_new), _ptr(v_new), _stream(k_text)))
+    return int(n_text) + 1
 
 
 def cq_bench_stream_read(buf: torch.Tensor, nbytes: int) -> None:

@@ -74,6 +74,20 @@ int hip_fail(hipError_t e, const char* what) {
 
 }  // namespace
 
+namespace {
+// one new token per (batch, KV head) row into slot n_text of the fp16 tails: 16 bytes per thread
+__global__ void __launch_bounds__(256) append_text_kernel(uint4* k_text, uint4* v_text, const uint4* k_new,
+                                                          const uint4* v_new, int rows, int n_text,
+                                                          int n_text_cap, int vec_per_token) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * vec_per_token) return;
+  const int row = i / vec_per_token, c = i % vec_per_token;
+  const size_t dst = ((size_t)row * n_text_cap + n_text) * vec_per_token + c;
+  k_text[dst] = k_new[i];
+  v_text[dst] = v_new[i];
+}
+}  // namespace
+
 extern "C" {
 
 int cq_version(void) { return 100; }
@@ -229,6 +243,34 @@ int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* 
     e = cq::launch_decode_generic(s, q_f16, kq, vq, k_text_f16, v_text_f16, c, softmax_scale,
                                   out_f16, static_cast<float*>(workspace), wl, st);
   if (e != hipSuccess) return hip_fail(e, "decode attention");
+  return CQ_OK;
+}
+
+int cq_append_text_kv(const cq_layout_t* L, void* k_text_f16, void* v_text_f16, int32_t n_text,
+                      int32_t n_text_cap, const void* k_new_f16, const void* v_new_f16,
+                      void* stream) {
+  int rc = check_layout(L, false);
+  if (rc != CQ_OK) return rc;
+  if (!k_text_f16 || !v_text_f16 || !k_new_f16 || !v_new_f16)
+    return fail(CQ_ERR_NULL, "a tail or new-token pointer is NULL");
+  if (!aligned16(k_text_f16) || !aligned16(v_text_f16) || !aligned16(k_new_f16) ||
+      !aligned16(v_new_f16))
+    return fail(CQ_ERR_ALIGN, "tails and new-token tensors must be 16-byte aligned");
+  if (n_text < 0 || n_text >= n_text_cap)
+    return fail(CQ_ERR_SHAPE, "the tail is full or n_text is negative: n_text=%d, n_text_cap=%d",
+                n_text, n_text_cap);
+  const long long rows = (long long)L->batch * L->n_kv_heads;
+  const int vec_per_token = L->head_dim * 2 / 16;          // head_dim is a multiple of 32
+  const long long n = rows * vec_per_token;
+  if (n == 0) return CQ_OK;
+  if (n > 0x7fffffffLL) return fail(CQ_ERR_SHAPE, "batch * n_kv_heads * head_dim is too large");
+  append_text_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream)>>>(
+      static_cast<uint4*>(k_text_f16), static_cast<uint4*>(v_text_f16),
+      static_cast<const uint4*>(k_new_f16), static_cast<const uint4*>(v_new_f16), (int)rows, n_text,
+      n_text_cap, vec_per_token);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(CQ_ERR_HIP, "append_text_kernel: %s", hipGetErrorString(e));
   return CQ_OK;
 }
 

@@ -90,6 +90,18 @@ def test_decode_argument_errors():
     assert cq.lib().cq_status_string(cq.CQ_ERR_WORKSPACE).startswith(b"CQ_ERR_WORKSPACE")
 
 
+def test_append_argument_errors():
+    lay = cq.make_layout(2, 8, 2, 128, 256)
+    f = cq.lib().cq_append_text_kv
+    assert f(ctypes.byref(lay), None, FAKE, 0, 4, FAKE, FAKE, None) == cq.CQ_ERR_NULL
+    assert f(ctypes.byref(lay), FAKE, FAKE, 0, 4, FAKE, None, None) == cq.CQ_ERR_NULL
+    assert f(ctypes.byref(lay), FAKE, FAKE + 2, 0, 4, FAKE, FAKE, None) == cq.CQ_ERR_ALIGN
+    assert f(ctypes.byref(lay), FAKE, FAKE, 4, 4, FAKE, FAKE, None) == cq.CQ_ERR_SHAPE   # tail full
+    assert f(ctypes.byref(lay), FAKE, FAKE, -1, 4, FAKE, FAKE, None) == cq.CQ_ERR_SHAPE
+    assert b"full" in cq.lib().cq_last_error()
+    assert f(None, FAKE, FAKE, 0, 4, FAKE, FAKE, None) == cq.CQ_ERR_NULL
+
+
 def test_workspace_size_rule():
     lay = cq.make_layout(2, 8, 2, 128, 1024)
     n = cq.cq_decode_workspace_bytes(lay, 32)

@@ -368,3 +368,41 @@ def test_full_size_long_context_config_on_sampled_rows(kernel_path, bits):
         got = out[b:b + 1, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)
         err = O.rel_l2(got, ref)
         assert err <= H.REL_L2_TOL, "row (%d,%d): rel L2 %.3e" % (b, h, err)
+
+
+def test_decoding_several_steps_with_a_growing_text_tail(kernel_path):
+    """Sec. 3: the quantized visual cache is fixed after the prefill while the fp16 tail grows by
+    one token per decode step.  cq_append_text_kv + cq_decode_attn over four steps against the
+    oracle on the same growing tail."""
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1280, n_text=61)
+    c = Case(w, H.layout_of(w))
+    cap = 64
+    B, Hkv, d = w.batch, w.n_kv_heads, w.head_dim
+    gen = torch.Generator().manual_seed(77)
+    k_tail = torch.zeros(B, Hkv, cap, d, dtype=torch.float16)
+    v_tail = torch.zeros(B, Hkv, cap, d, dtype=torch.float16)
+    k_tail[:, :, :w.n_text] = c.x_cpu["k_text"]
+    v_tail[:, :, :w.n_text] = c.x_cpu["v_text"]
+    k_dev, v_dev = k_tail.cuda(), v_tail.cuda()
+    n_text = w.n_text
+    calib = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    for step in range(4):
+        q = torch.randn(B, w.n_q_heads, d, generator=gen).to(torch.float16)
+        out = cq.cq_decode_attn(c.lay, q.cuda(), c.k_dev, c.v_dev, k_dev, v_dev, n_text, calib)
+        torch.cuda.synchronize()
+        ref = O.decode_attn(q.numpy(), c.kq, c.vq, k_tail.numpy(), v_tail.numpy(), n_text,
+                            O.CALIB_DYNAMIC, 1.0, 2.0)
+        err = O.rel_l2(out.cpu().numpy().astype(np.float64), ref)
+        assert err <= H.REL_L2_TOL, "step %d: rel L2 %.3e" % (step, err)
+        if n_text == cap:
+            with pytest.raises(cq.CqError):
+                cq.cq_append_text_kv(c.lay, k_dev, v_dev, n_text, k_dev[:, :, :1].contiguous(),
+                                     v_dev[:, :, :1].contiguous())
+            break
+        k_new = torch.randn(B, Hkv, 1, d, generator=gen).to(torch.float16)
+        v_new = torch.randn(B, Hkv, 1, d, generator=gen).to(torch.float16)
+        k_tail[:, :, n_text] = k_new[:, :, 0]
+        v_tail[:, :, n_text] = v_new[:, :, 0]
+        n_text = cq.cq_append_text_kv(c.lay, k_dev, v_dev, n_text, k_new.cuda(), v_new.cuda())
+        torch.cuda.synchronize()
+        assert torch.equal(k_dev.cpu(), k_tail) and torch.equal(v_dev.cpu(), v_tail)
