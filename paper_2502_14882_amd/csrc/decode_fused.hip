@@ -160,10 +160,12 @@ __device__ inline float dpp_f32(float v) {
 // w, which inv_w = 1/w takes out again).  A transposing butterfly leaves lane (.., b1, b0) with head
 // 2*b0 + b1 after two steps, the remaining steps add lanes that hold the same head; the result
 // lane of head kb = lane / 16 then fetches its head.
+// off0/off1: what the operand bytes leave out per channel (128 * scale for 8-bit codes, else 0).
 __device__ inline float group_bias(const float (&qv0)[kHeads], const float (&qv1)[kHeads],
-                                   uint16_t m0, uint16_t m1, float inv_w, int lane) {
-  const float f0 = __half2float(__ushort_as_half(m0)) * inv_w;
-  const float f1 = __half2float(__ushort_as_half(m1)) * inv_w;
+                                   uint16_t m0, uint16_t m1, float off0, float off1, float inv_w,
+                                   int lane) {
+  const float f0 = (__half2float(__ushort_as_half(m0)) + off0) * inv_w;
+  const float f1 = (__half2float(__ushort_as_half(m1)) + off1) * inv_w;
   float part[kHeads];
 #pragma unroll
   for (int h = 0; h < kHeads; ++h) part[h] = fmaf(qv0[h], f0, qv1[h] * f1);
@@ -204,22 +206,36 @@ __device__ inline int product_digits(float a, float b) {
 
 extern __shared__ __align__(16) uint8_t smem[];
 
-// Masks that turn a packed word into int8 operands, and what an operand byte is worth.
-//   b = 1: variant p in 0..7, mask 0x01010101 << p, byte = bit * 2^p (-128 for p = 7)
-//   b = 2: variant v in 0..3, masks 0x03 / 0x0c / 0x30 per byte and (word >> 2) & 0x30 for the top
+// Masks that turn a packed word into int8 operands, and what an operand byte is worth.  A byte
+// of a word holds 8 / b codes; variant v picks code v of every byte (from the low bits up):
+//   b = 1: v in 0..7, mask 0x01010101 << v, byte = bit * 2^v (-128 for v = 7)
+//   b = 2: v in 0..3, masks 0x03 / 0x0c / 0x30 per byte and (word >> 2) & 0x30 for the top
 //          code of each byte, byte = code * {1, 4, 16, 16}
+//   b = 4: v in 0..1, word & 0x0f.. and (word >> 4) & 0x0f.., byte = code
+//   b = 8: the byte is the code; word ^ 0x80.. is code - 128 as int8, and the 128 is added back
+//          through the additive term (it multiplies the same scale)
 template <int BITS>
 __device__ inline int operand_variant(uint32_t word, int v) {
   if constexpr (BITS == 1) return (int)(word & (0x01010101u << v));
-  else return v < 3 ? (int)(word & (0x03030303u << (2 * v))) : (int)((word >> 2) & 0x30303030u);
+  else if constexpr (BITS == 2)
+    return v < 3 ? (int)(word & (0x03030303u << (2 * v))) : (int)((word >> 2) & 0x30303030u);
+  else if constexpr (BITS == 4) return (int)((v ? word >> 4 : word) & 0x0f0f0f0fu);
+  else return (int)(word ^ 0x80808080u);
 }
 template <int BITS>
 __device__ inline float variant_weight(int v) {     // 1 / (value of a set code-1 byte)
   if constexpr (BITS == 1) return ldexpf(1.f, -v) * (v == 7 ? -1.f : 1.f);
-  else return v == 0 ? 1.f : v == 1 ? 0.25f : 0.0625f;
+  else if constexpr (BITS == 2) return v == 0 ? 1.f : v == 1 ? 0.25f : 0.0625f;
+  else return 1.f;
+}
+// Position, inside its 32-bit word, of the code that variant v reads from byte y: the packing is
+// MSB first, so code j sits at bits [32 - b(1 + j), 32 - b j).
+template <int BITS>
+__device__ inline int code_in_word(int y, int v) {
+  return (32 / BITS - 1) - ((8 / BITS) * y + v);
 }
 
-// TILES = 16-token tiles per key group (k_group / 16); BITS = code width (1 or 2); VCH = values
+// TILES = 16-token tiles per key group (k_group / 16); BITS = code width (1, 2, 4 or 8); VCH = values
 // quantized channel-wise over groups of tokens (Sec. 3.1, the paper's own choice) instead of
 // token-wise.
 template <int TILES, int BITS, bool VCH>
@@ -303,16 +319,18 @@ fused_row_kernel(const FusedArgs a) {
     const int hres = kb;
     float mn = FLT_MAX, mx = -FLT_MAX;
     if (nv > 0) {
-      // operand rows: r = ((kb*2 + i)*4 + v)*4 + y, i = matrix, v = register, y = byte.
-      //   b = 1: lane (n16, kb) holds word kb of its token; row r <-> channel
-      //          32kb + 31 - (4i+v) - 8y, mask variant 4i + v;
-      //   b = 2: it holds words 2kb and 2kb+1, matrix i takes word 2kb + i; row r <-> channel
-      //          32kb + 16i + 15 - 4y - v, mask variant v.
+      // operand rows: r = ((kb*2 + i)*4 + v)*4 + y, i = matrix, v = register, y = byte.  Lane
+      // (n16, kb) holds words kb*b .. kb*b + b-1 of its token = channels 32kb .. 32kb + 31:
+      //   b = 1: row r <-> channel 32kb + 31 - (4i+v) - 8y, mask variant 4i + v;
+      //   b = 2: matrix i takes word 2kb + i; row r <-> channel 32kb + 16i + 15 - 4y - v;
+      //   b = 4: matrix i takes words 4kb + 2i, +1, two variants each; b = 8: words 8kb + 4i .. +3.
       // Row r lives at base + (r / 32) * pitch + (r % 32) * 16.
+      // register v of matrix i is pair 4i + v of the lane's 8 (word, variant) pairs:
+      // word (4i + v) / (8/b) of the lane's b words, variant (4i + v) % (8/b)
       const int wi = (lane >> 3) & 1, wv = (lane >> 1) & 3, wy = (lane & 1) * 2;
-      const int wvar = BITS == 1 ? 4 * wi + wv : wv;
-      const int wc0 = BITS == 1 ? 32 * kb + 31 - wvar - 8 * wy : 32 * kb + 16 * wi + 15 - 4 * wy - wv;
-      const int wc1 = wc0 - (BITS == 1 ? 8 : 4);
+      const int wpair = 4 * wi + wv, wword = wpair / (8 / BITS), wvar = wpair % (8 / BITS);
+      const int wc0 = 32 * kb + (32 / BITS) * wword + code_in_word<BITS>(wy, wvar);
+      const int wc1 = wc0 - 8 / BITS;                 // byte wy + 1
       float qv0[kHeads], qv1[kHeads];
 #pragma unroll
       for (int h = 0; h < kHeads; ++h) {
@@ -331,9 +349,12 @@ fused_row_kernel(const FusedArgs a) {
       const int x_wr = (lane >> 4) * pitch + ((2 * lane) & 31) * 16;
       const int x_rd = kb * pitch + (n16 >> 1) * 16 + (n16 & 1) * 8;
 
-      uint32_t w[kRingK][TILES][BITS];
-      float s0[kRingK], s1[kRingK];
-      uint16_t m0[kRingK], m1[kRingK];
+      // wide codes are 4 or 8 words per lane and tile: one group in the ring is all that fits
+      // (the depth of this ring was measured to make no difference)
+      constexpr int kRK = BITS > 2 ? 1 : kRingK;
+      uint32_t w[kRK][TILES][BITS];
+      float s0[kRK], s1[kRK];
+      uint16_t m0[kRK], m1[kRK];
       auto load_group = [&](int slot, int t) {
         const int tc = min(t, n_groups - 1);      // clamped, never a branch around a load
 #pragma unroll
@@ -370,20 +391,17 @@ fused_row_kernel(const FusedArgs a) {
         const v2i r10 = lds_read_tr8(xr + 256), r11 = lds_read_tr8(xr + 384);
         const v4i A0 = {r00[0], r00[1], r01[0], r01[1]};
         const v4i A1 = {r10[0], r10[1], r11[0], r11[1]};
-        const float bias_h = group_bias(qv0, qv1, m0[slot], m1[slot], inv_w, lane);
+        const float bias_h = group_bias(qv0, qv1, m0[slot], m1[slot], BITS == 8 ? 128.f * s0[slot] : 0.f,
+                                        BITS == 8 ? 128.f * s1[slot] : 0.f, inv_w, lane);
         __builtin_amdgcn_wave_barrier();   // operand rows are consumed before logits land there
         // the operands of tile + 1 are formed before the products of this tile are issued, so no
         // product waits on the ANDs right in front of it
         auto expand = [&](int tile, v4i& B0, v4i& B1) {
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            if constexpr (BITS == 1) {
-              B0[v] = operand_variant<1>(w[slot][tile][0], v);
-              B1[v] = operand_variant<1>(w[slot][tile][0], 4 + v);
-            } else {
-              B0[v] = operand_variant<2>(w[slot][tile][0], v);
-              B1[v] = operand_variant<2>(w[slot][tile][1], v);
-            }
+            constexpr int kV = 8 / BITS;            // variants per byte
+            B0[v] = operand_variant<BITS>(w[slot][tile][v / kV], v % kV);
+            B1[v] = operand_variant<BITS>(w[slot][tile][(4 + v) / kV], (4 + v) % kV);
           }
         };
         auto finish_tile = [&](int tile, const v4i& c) {
@@ -415,21 +433,21 @@ fused_row_kernel(const FusedArgs a) {
         }
       };
 #pragma unroll
-      for (int d = 0; d < kRingK; ++d) load_group(d, wave + d * kVisWaves);
+      for (int d = 0; d < kRK; ++d) load_group(d, wave + d * kVisWaves);
       pin_order();
       int t = wave;
-      for (; t + (kRingK - 1) * kVisWaves < n_groups; t += kRingK * kVisWaves) {
+      for (; t + (kRK - 1) * kVisWaves < n_groups; t += kRK * kVisWaves) {
 #pragma unroll
-        for (int d = 0; d < kRingK; ++d) {          // no branch around the ring's loads
+        for (int d = 0; d < kRK; ++d) {             // no branch around the ring's loads
           const int tt = t + d * kVisWaves;
           do_group(d, tt);
           pin_order();
-          load_group(d, tt + kRingK * kVisWaves);
+          load_group(d, tt + kRK * kVisWaves);
           pin_order();
         }
       }
 #pragma unroll
-      for (int d = 0; d < kRingK; ++d)              // the wave's last groups, already loaded
+      for (int d = 0; d < kRK; ++d)                 // the wave's last groups, already loaded
         if (t + d * kVisWaves < n_groups) do_group(d, t + d * kVisWaves);
     }
     CQ_CLK(2);
@@ -657,8 +675,7 @@ fused_row_kernel(const FusedArgs a) {
           v4i B;
 #pragma unroll
           for (int v = 0; v < 4; ++v)
-            B[v] = BITS == 1 ? operand_variant<1>((uint32_t)raw[0][v], p)
-                             : operand_variant<2>((uint32_t)raw[p >> 2][v], p & 3);
+            B[v] = operand_variant<BITS>((uint32_t)raw[p / (8 / BITS)][v], p % (8 / BITS));
           return B;
         };
         v4i Bn = variant_of(0);
@@ -681,7 +698,7 @@ fused_row_kernel(const FusedArgs a) {
             const uint32_t mpair = (uint32_t)gmn[vec][el >> 1];
             const float mn = __half2float(__ushort_as_half((uint16_t)((el & 1) ? mpair >> 16 : mpair & 0xffffu)));
             // the operand byte of a set code is 2^p (b = 1) resp. code * {1, 4, 16, 16}: take that out
-            const float sc = gsc[vec][el] * variant_weight<BITS>(BITS == 1 ? p : (p & 3));
+            const float sc = gsc[vec][el] * variant_weight<BITS>(p % (8 / BITS));
             facc[p] = fmaf(digits_to_float(acc[p]), sc, fmaf(wsum, mn, facc[p]));
             acc[p] = (v4i){0, 0, 0, 0};
           }
@@ -707,7 +724,96 @@ fused_row_kernel(const FusedArgs a) {
       }
       Fv = 0;
     } }
-    if constexpr (!VCH) { if (nv > 0) {
+    if constexpr (!VCH && BITS > 2) { if (nv > 0) {
+      // 4- and 8-bit codes: a tile's code bytes (64 or 128 per token) go through the wave's 2 KB
+      // staging buffer two column blocks at a time, straight from the ring registers; the steps
+      // of a tile run one after the other (these widths are bound by their bytes, not by issue).
+      constexpr int kV = 8 / BITS;
+      int F_prep = 90, F_acc = 90;
+      float fit_below = ldexpf(1.f, 29 - 90);
+      const uint32_t* vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS);
+      const int step = kVisWaves * 64, last = nv - 64;
+      const int x_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;
+      const int x_rd = (kb * a.stride) * 4 + (n16 >> 1) * 16 + (n16 & 1) * 8;
+      const int v_rd = (kb * 16 + (n16 >> 1)) * 32 + (n16 & 1) * 8;     // 32-byte rows: two blocks
+      v4i cg[2][BITS];
+      float vsr[2];
+      uint16_t vmr[2];
+      auto load_tile = [&](int slot, int jt) {
+        const int j = min(jt, last) + lane;
+#pragma unroll
+        for (int e = 0; e < BITS; ++e)
+          cg[slot][e] = *reinterpret_cast<const v4i*>(vc_row + (size_t)j * (4 * BITS) + 4 * e);
+        vsr[slot] = vs_row[j];
+        vmr[slot] = vm_row[j];
+      };
+      auto tile_step = [&](int jt, int slot) {
+        if (__builtin_amdgcn_ballot_w64(vsr[slot] >= fit_below) != 0) {
+          F_prep = min(F_prep, fixed_point_shift(wave_max_nonneg(vsr[slot])));
+          fit_below = ldexpf(1.f, 29 - F_prep);
+        }
+        if (F_prep < F_acc) {                     // bank before a tile with a lower shift is added
+          const float w_old = ldexpf(1.f, -F_acc);
+#pragma unroll
+          for (int p = 0; p < 8; ++p) {
+            facc[p] = fmaf(digits_to_float(acc[p]), w_old, facc[p]);
+            acc[p] = (v4i){0, 0, 0, 0};
+          }
+          F_acc = F_prep;
+        }
+        const float vsf = ldexpf(vsr[slot], F_prep);
+        // 8-bit operands are code - 128: the 128 comes back with the token's minimum
+        const float vmf = __half2float(__ushort_as_half(vmr[slot])) + (BITS == 8 ? 128.f * vsr[slot] : 0.f);
+        v4i xs;
+#pragma unroll
+        for (int h = 0; h < kHeads; ++h) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(logits[h * a.stride + jt + lane], a2[h], c2v[h]));
+          lsum[h] += p;
+          msum[h] = fmaf(p, vmf, msum[h]);
+          xs[h] = product_digits(p, vsf);
+        }
+        __builtin_amdgcn_wave_barrier();
+        *reinterpret_cast<v4i*>(lbytes + (size_t)jt * 4 + x_wr) = xs;
+        lds_publish();
+        const uint8_t* xr = lbytes + (size_t)jt * 4 + x_rd;
+        const v2i a_lo = lds_read_tr8(xr), a_hi = lds_read_tr8(xr + 128);
+        const v4i A = {a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
+#pragma unroll
+        for (int r = 0; r < BITS / 2; ++r) {
+          __builtin_amdgcn_wave_barrier();
+          *reinterpret_cast<v4i*>(stage + lane * 32) = cg[slot][2 * r];
+          *reinterpret_cast<v4i*>(stage + lane * 32 + 16) = cg[slot][2 * r + 1];
+          lds_publish();
+#pragma unroll
+          for (int cbl = 0; cbl < 2; ++cbl) {
+            const v2i b_lo = lds_read_tr8(stage + v_rd + 16 * cbl);
+            const v2i b_hi = lds_read_tr8(stage + v_rd + 16 * cbl + 256);
+            const v4i raw = {b_lo[0], b_lo[1], b_hi[0], b_hi[1]};
+#pragma unroll
+            for (int v = 0; v < kV; ++v) {
+              v4i B;
+#pragma unroll
+              for (int u = 0; u < 4; ++u) B[u] = operand_variant<BITS>((uint32_t)raw[u], v);
+              const int p = (2 * r + cbl) * kV + v;
+              acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B, acc[p], 0, 0, 0);
+            }
+          }
+        }
+        pin_order();
+        load_tile(slot, jt + 2 * step);
+        pin_order();
+      };
+      const int j_first = wave * 64;
+      load_tile(0, j_first);
+      load_tile(1, j_first + step);
+      pin_order();
+      for (int j0 = j_first; j0 < nv; j0 += 2 * step) {
+        tile_step(j0, 0);
+        if (j0 + step < nv) tile_step(j0 + step, 1);
+      }
+      Fv = F_acc;
+    } }
+    if constexpr (!VCH && BITS <= 2) { if (nv > 0) {
       // Pipeline over 64-token tiles (tile k of this wave starts at token (wave + 8k) * 64):
       //   G(k)  global loads of the tile's codes, scale and min into a ring of registers
       //   P(k)  weights p = 2^(a2*s + c2) from the logits in LDS, their fixed-point digits X(k)
@@ -813,8 +919,7 @@ fused_row_kernel(const FusedArgs a) {
           v4i B;
 #pragma unroll
           for (int v = 0; v < 4; ++v)
-            B[v] = BITS == 1 ? operand_variant<1>((uint32_t)raw[0][v], p)
-                             : operand_variant<2>((uint32_t)raw[p >> 2][v], p & 3);
+            B[v] = operand_variant<BITS>((uint32_t)raw[p / (8 / BITS)][v], p % (8 / BITS));
           return B;
         };
         v4i Bn = variant_of(0);
@@ -916,11 +1021,13 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
       const float v = fmaf(digits_to_float(acc[p]), inv_fv, facc[p]);
-      // column n16 of accumulator p is code byte n16 (b = 1) or 16 * (p / 4) + n16 (b = 2)
-      const int ch = BITS == 1 ? 32 * (n16 >> 2) + 31 - 8 * (n16 & 3) - p
-                               : 64 * (p >> 2) + 16 * (n16 >> 2) + 15 - 4 * (n16 & 3) - (p & 3);
+      // accumulator p = (column block cb, variant v) = (p / (8/b), p % (8/b)); its column n16 is byte
+      // 16 cb + n16 of the token's code bytes
+      constexpr int kV = 8 / BITS;
+      const int tb = 16 * (p / kV) + n16;
+      const int ch = (32 / BITS) * (tb >> 2) + code_in_word<BITS>(tb & 3, p % kV);
       // channel-wise values are accumulated in units of 2^-29 (the weights' fixed point)
-      partial[kb * kD + ch] = VCH ? v * 0x1p-29f : v * variant_weight<BITS>(BITS == 1 ? p : (p & 3));
+      partial[kb * kD + ch] = VCH ? v * 0x1p-29f : v * variant_weight<BITS>(p % kV);
     }
   } else if (kb == 0) {
 #pragma unroll
@@ -1040,7 +1147,8 @@ void chunk_extent(const DecodeShape& s, int n_chunks, int* nv_max, int* nt_max) 
 
 FusedPlan make_plan(const DecodeShape& s, size_t workspace_bytes) {
   FusedPlan p;
-  if (s.d != kD || (s.bits != 1 && s.bits != 2)) return p;
+  if (s.d != kD || (s.bits != 1 && s.bits != 2 && s.bits != 4 && s.bits != 8)) return p;
+  if (s.bits > 2 && s.v_axis != CQ_AXIS_TOKEN) return p;     // wide codes: token-wise values only
   if (s.k_axis != CQ_AXIS_CHANNEL) return p;
   if (s.v_axis == CQ_AXIS_TOKEN ? s.v_group != kD : (s.v_group != 64 && s.v_group != 128)) return p;
   if (s.k_group != 32 && s.k_group != 64 && s.k_group != 128) return p;
@@ -1155,11 +1263,17 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
     case (32 * 4 + 2) * 2 + 1: kern = fused_row_kernel<2, 2, true>; slot = 9; break;
     case (64 * 4 + 2) * 2 + 1: kern = fused_row_kernel<4, 2, true>; slot = 10; break;
     case (128 * 4 + 2) * 2 + 1: kern = fused_row_kernel<8, 2, true>; slot = 11; break;
+    case (32 * 4 + 4) * 2: kern = fused_row_kernel<2, 4, false>; slot = 12; break;
+    case (64 * 4 + 4) * 2: kern = fused_row_kernel<4, 4, false>; slot = 13; break;
+    case (128 * 4 + 4) * 2: kern = fused_row_kernel<8, 4, false>; slot = 14; break;
+    case (32 * 4 + 8) * 2: kern = fused_row_kernel<2, 8, false>; slot = 15; break;
+    case (64 * 4 + 8) * 2: kern = fused_row_kernel<4, 8, false>; slot = 16; break;
+    case (128 * 4 + 8) * 2: kern = fused_row_kernel<8, 8, false>; slot = 17; break;
     default: return hipErrorInvalidValue;
   }
   // the kernel's dynamic LDS limit is raised once per (device, kernel) and only ever grows;
   // concurrent callers may both raise it, which is harmless
-  static std::atomic<size_t> configured[kMaxDevices][12];
+  static std::atomic<size_t> configured[kMaxDevices][18];
   int dev = 0;
   hipError_t de = hipGetDevice(&dev);
   if (de != hipSuccess) return de;

@@ -406,3 +406,42 @@ def test_decoding_several_steps_with_a_growing_text_tail(kernel_path):
         n_text = cq.cq_append_text_kv(c.lay, k_dev, v_dev, n_text, k_new.cuda(), v_new.cuda())
         torch.cuda.synchronize()
         assert torch.equal(k_dev.cpu(), k_tail) and torch.equal(v_dev.cpu(), v_tail)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("kg", [32, 64, 128])
+def test_tuned_wide_codes(kernel_path, bits, kg):
+    """4- and 8-bit codes on the tuned kernels (nibbles and bytes as matrix operands, the
+    offset of the 8-bit operand carried by the additive terms): g = 4 and g = 6, every mode."""
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    cases = []
+    for w in (synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1536, n_text=200),
+              synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=1280, n_text=70)):
+        cases.append(Case(w, H.layout_of(w, bits, kg, 128)))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        for c in cases:
+            c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+            c.check(cq.CQ_CALIB_NONE)
+            c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, n_text=0)
+    finally:
+        cq.cq_set_kernel_path(prev)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_tuned_wide_codes_on_split_and_full_length_rows(kernel_path, bits, monkeypatch):
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    w_full = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8)
+    full = Case(w_full, H.layout_of(w_full, bits))
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200)
+    split = Case(w, H.layout_of(w, bits))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        full.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+        monkeypatch.setenv("CQ_DECODE_CHUNKS", "3")
+        split.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+        split.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
+    finally:
+        cq.cq_set_kernel_path(prev)
