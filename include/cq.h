@@ -60,7 +60,7 @@ typedef struct {
   int32_t n_kv_heads; /* Hkv >= 1 */
   int32_t head_dim;   /* d: multiple of 32 in [32, 256]; 128 is the tuned case */
   int32_t n_vis;      /* quantized (visual) tokens per sequence, >= 0 */
-  int32_t bits;       /* b in {1, 2, 4, 8}; 1 and 2 are the tuned cases */
+  int32_t bits;       /* b in {1, 2, 4, 8} */
   int32_t k_axis;     /* CQ_AXIS_* for keys   (hot path: CHANNEL) */
   int32_t v_axis;     /* CQ_AXIS_* for values (hot path: TOKEN) */
   int32_t k_group;    /* CHANNEL axis: tokens per group, divides n_vis;
