@@ -445,3 +445,40 @@ def test_tuned_wide_codes_on_split_and_full_length_rows(kernel_path, bits, monke
         split.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
     finally:
         cq.cq_set_kernel_path(prev)
+
+
+def test_random_layouts_on_the_tuned_kernels(kernel_path, monkeypatch):
+    """Seeded sweep over the layouts the tuned kernels accept: code width, group sizes, value
+    axis, heads per KV head (1..8), ragged text tails, forced row splits, calibration modes."""
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    rng = np.random.default_rng(2024)
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        for trial in range(24):
+            bits = int(rng.choice([1, 2, 4, 8]))
+            kg = int(rng.choice([32, 64, 128]))
+            vch = bits <= 2 and rng.random() < 0.4
+            vg = int(rng.choice([64, 128])) if vch else 128
+            g = int(rng.integers(1, 9))
+            hkv = int(rng.integers(1, 3))
+            n_vis = 128 * int(rng.integers(1, 13))
+            n_text = int(rng.choice([0, 1, 15, 16, 17, 63, 64, 65, 130, 257]))
+            chunks = int(rng.choice([1, 1, 2, 3]))
+            unit = max(128, vg if vch else 64, kg)
+            if n_vis // unit < chunks:
+                chunks = 1
+            monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
+            w = synth.WORKLOADS[int(rng.choice([1, 4]))].replace(
+                batch=int(rng.integers(1, 3)), n_kv_heads=hkv, n_q_heads=hkv * g, n_vis=n_vis,
+                n_text=n_text, seed=5000 + trial)
+            c = Case(w, H.layout_of(w, bits, kg, vg, 0, 0 if vch else 1))
+            mode = int(rng.choice([cq.CQ_CALIB_NONE, cq.CQ_CALIB_DYNAMIC, cq.CQ_CALIB_FIXED]))
+            try:
+                c.check(mode, float(rng.integers(0, 4)), float(rng.integers(0, 4)), gamma=-25.0, delta=25.0)
+            except AssertionError as e:
+                raise AssertionError("trial %d (bits %d kg %d vg %d vch %s g %d hkv %d n_vis %d n_text %d "
+                                     "chunks %d mode %d): %s" % (trial, bits, kg, vg, vch, g, hkv, n_vis,
+                                                                 n_text, chunks, mode, e))
+    finally:
+        cq.cq_set_kernel_path(prev)

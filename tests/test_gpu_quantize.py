@@ -191,3 +191,25 @@ def test_wide_codes_round_exact_ties_to_even_on_the_tuned_path(kernel_path, bits
             _run(w, H.layout_of(w, bits, group, group, 1, 0), x, what="ties swapped b=%d" % bits)
     finally:
         cq.cq_set_kernel_path(prev)
+
+
+def test_random_layouts_on_the_tuned_quantizer(kernel_path):
+    """Seeded sweep over what the tuned quantizer accepts: code width, group size, either axis for
+    keys and values, row counts and lengths; heavy-tailed and outlier inputs; bit-exact."""
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    rng = np.random.default_rng(99)
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        for trial in range(20):
+            bits = int(rng.choice([1, 2, 4, 8]))
+            kg, vg = int(rng.choice([32, 64, 128])), int(rng.choice([32, 64, 128]))
+            ka, va = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+            w = synth.WORKLOADS[int(rng.choice([1, 3, 4]))].replace(
+                batch=int(rng.integers(1, 4)), n_kv_heads=int(rng.integers(1, 4)), n_q_heads=1,
+                n_vis=128 * int(rng.integers(1, 9)), seed=7000 + trial)
+            w = w.replace(n_q_heads=w.n_kv_heads)
+            _run(w, H.layout_of(w, bits, kg, vg, ka, va),
+                 what="trial %d b=%d kg=%d vg=%d axes=%d%d" % (trial, bits, kg, vg, ka, va))
+    finally:
+        cq.cq_set_kernel_path(prev)
