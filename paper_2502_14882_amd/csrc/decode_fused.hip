@@ -36,6 +36,7 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
 constexpr int kD = 128;             // head_dim
@@ -157,15 +158,15 @@ __device__ inline float dpp_f32(float v) {
 
 // Additive post-scaling term of one key group, sum_c q'[h][c] * min[c] for the four heads.  Every
 // lane brings two channels (q' already carries the softmax scale and the lane's operand weight
-// w, which inv_w = 1/w takes out again).  A transposing butterfly leaves lane (.., b1, b0) with head
+// w, which inv_w = 1/w takes out again, per channel).  A transposing butterfly leaves lane (.., b1, b0) with head
 // 2*b0 + b1 after two steps, the remaining steps add lanes that hold the same head; the result
 // lane of head kb = lane / 16 then fetches its head.
 // off0/off1: what the operand bytes leave out per channel (128 * scale for 8-bit codes, else 0).
 __device__ inline float group_bias(const float (&qv0)[kHeads], const float (&qv1)[kHeads],
-                                   uint16_t m0, uint16_t m1, float off0, float off1, float inv_w,
-                                   int lane) {
-  const float f0 = (__half2float(__ushort_as_half(m0)) + off0) * inv_w;
-  const float f1 = (__half2float(__ushort_as_half(m1)) + off1) * inv_w;
+                                   uint16_t m0, uint16_t m1, float off0, float off1, float inv_w0,
+                                   float inv_w1, int lane) {
+  const float f0 = (__half2float(__ushort_as_half(m0)) + off0) * inv_w0;
+  const float f1 = (__half2float(__ushort_as_half(m1)) + off1) * inv_w1;
   float part[kHeads];
 #pragma unroll
   for (int h = 0; h < kHeads; ++h) part[h] = fmaf(qv0[h], f0, qv1[h] * f1);
@@ -326,19 +327,28 @@ fused_row_kernel(const FusedArgs a) {
       //   b = 4: matrix i takes words 4kb + 2i, +1, two variants each; b = 8: words 8kb + 4i .. +3.
       // Row r lives at base + (r / 32) * pitch + (r % 32) * 16.
       // register v of matrix i is pair 4i + v of the lane's 8 (word, variant) pairs:
-      // word (4i + v) / (8/b) of the lane's b words, variant (4i + v) % (8/b)
-      const int wi = (lane >> 3) & 1, wv = (lane >> 1) & 3, wy = (lane & 1) * 2;
-      const int wpair = 4 * wi + wv, wword = wpair / (8 / BITS), wvar = wpair % (8 / BITS);
-      const int wc0 = 32 * kb + (32 / BITS) * wword + code_in_word<BITS>(wy, wvar);
-      const int wc1 = wc0 - 8 / BITS;                 // byte wy + 1
+      // word (4i + v) / (8/b) of the lane's b words, variant (4i + v) % (8/b).
+      // Writing the rows is a job of its own: lane (kb, l) writes the rows of the two ADJACENT
+      // channels 32kb + 2l and + 1, so that their scales (one 8-byte load) and minima (one 4-byte
+      // load) come in fully coalesced; which rows those are follows from inverting the map above.
+      constexpr int kV = 8 / BITS, kCW = 32 / BITS;       // variants per byte, codes per word
+      const int wc0 = 32 * kb + 2 * n16, wc1 = wc0 + 1;
+      auto row_of = [&](int c, int& variant) {            // row inside the kb block, and its variant
+        const int cl = c & 31, e = cl / kCW, t = kCW - 1 - cl % kCW;
+        const int y = t / kV, v = t % kV, pair = e * kV + v;
+        variant = v;
+        return pair * 4 + y;
+      };
+      int wvar0, wvar1;
+      const int wr0 = row_of(wc0, wvar0), wr1 = row_of(wc1, wvar1);
       float qv0[kHeads], qv1[kHeads];
 #pragma unroll
       for (int h = 0; h < kHeads; ++h) {
-        const float f = a.softmax_scale * variant_weight<BITS>(wvar);
-        qv0[h] = qf[h * kD + wc0] * f;
-        qv1[h] = qf[h * kD + wc1] * f;
+        qv0[h] = qf[h * kD + wc0] * (a.softmax_scale * variant_weight<BITS>(wvar0));
+        qv1[h] = qf[h * kD + wc1] * (a.softmax_scale * variant_weight<BITS>(wvar1));
       }
-      const float inv_w = 1.f / variant_weight<BITS>(wvar);     // exact: a power of two
+      const float inv_w0 = 1.f / variant_weight<BITS>(wvar0);   // exact: powers of two
+      const float inv_w1 = 1.f / variant_weight<BITS>(wvar1);
       const uint32_t* kc_lane =
           a.k_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS) + n16 * (4 * BITS) + kb * BITS;
       float* lrow = logits + (size_t)hres * a.stride + n16;
@@ -346,15 +356,15 @@ fused_row_kernel(const FusedArgs a) {
       // slots (2 KB, not yet written); smaller groups use the wave's staging buffer
       constexpr bool kInPlace = (TILES == 8);
       const int pitch = kInPlace ? a.stride * 4 : 512;
-      const int x_wr = (lane >> 4) * pitch + ((2 * lane) & 31) * 16;
+      const int x_wr0 = kb * pitch + wr0 * 16, x_wr1 = kb * pitch + wr1 * 16;
       const int x_rd = kb * pitch + (n16 >> 1) * 16 + (n16 & 1) * 8;
 
       // wide codes are 4 or 8 words per lane and tile: one group in the ring is all that fits
       // (the depth of this ring was measured to make no difference)
       constexpr int kRK = BITS > 2 ? 1 : kRingK;
       uint32_t w[kRK][TILES][BITS];
-      float s0[kRK], s1[kRK];
-      uint16_t m0[kRK], m1[kRK];
+      v2f s01[kRK];               // scales of channels wc0, wc1
+      uint32_t m01[kRK];          // their minima, two fp16 in one word
       auto load_group = [&](int slot, int t) {
         const int tc = min(t, n_groups - 1);      // clamped, never a branch around a load
 #pragma unroll
@@ -362,17 +372,16 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
           for (int e = 0; e < BITS; ++e)
             w[slot][i][e] = kc_lane[((size_t)tc * TILES + i) * (64 * BITS) + e];
-        s0[slot] = ks_row[(size_t)tc * kD + wc0];
-        s1[slot] = ks_row[(size_t)tc * kD + wc1];
-        m0[slot] = km_row[(size_t)tc * kD + wc0];
-        m1[slot] = km_row[(size_t)tc * kD + wc1];
+        s01[slot] = *reinterpret_cast<const v2f*>(ks_row + (size_t)tc * kD + wc0);
+        m01[slot] = *reinterpret_cast<const uint32_t*>(km_row + (size_t)tc * kD + wc0);
       };
       auto do_group = [&](int slot, int t) {
         // |q'| <= max|q| * (largest scale of the group): a bound, good to a few bits, that costs
         // one wave-wide maximum instead of a pass over all scales
-        const float smax = wave_max_nonneg(fmaxf(s0[slot], s1[slot]));
+        const float s0 = s01[slot][0], s1 = s01[slot][1];
+        const float smax = wave_max_nonneg(fmaxf(s0, s1));
         const int F = fixed_point_shift(qmax_all * smax);      // one shift for the four heads
-        const float s0f = ldexpf(s0[slot], F), s1f = ldexpf(s1[slot], F);
+        const float s0f = ldexpf(s0, F), s1f = ldexpf(s1, F);
         v4i x0, x1;
 #pragma unroll
         for (int h = 0; h < kHeads; ++h) {
@@ -382,8 +391,8 @@ fused_row_kernel(const FusedArgs a) {
         const float inv_f = ldexpf(1.f, -F), inv_f16 = ldexpf(1.f, 16 - F);
         uint8_t* xb = kInPlace ? lbytes + (size_t)t * (TILES * 16 * 4) : stage;
         __builtin_amdgcn_wave_barrier();
-        *reinterpret_cast<v4i*>(xb + x_wr) = x0;
-        *reinterpret_cast<v4i*>(xb + x_wr + 16) = x1;
+        *reinterpret_cast<v4i*>(xb + x_wr0) = x0;
+        *reinterpret_cast<v4i*>(xb + x_wr1) = x1;
         lds_publish();
         // A operand of matrix i: rows (kb*2 + i)*16 .. +15, two transposing reads of 8 rows
         const uint8_t* xr = xb + x_rd;
@@ -391,8 +400,9 @@ fused_row_kernel(const FusedArgs a) {
         const v2i r10 = lds_read_tr8(xr + 256), r11 = lds_read_tr8(xr + 384);
         const v4i A0 = {r00[0], r00[1], r01[0], r01[1]};
         const v4i A1 = {r10[0], r10[1], r11[0], r11[1]};
-        const float bias_h = group_bias(qv0, qv1, m0[slot], m1[slot], BITS == 8 ? 128.f * s0[slot] : 0.f,
-                                        BITS == 8 ? 128.f * s1[slot] : 0.f, inv_w, lane);
+        const float bias_h = group_bias(qv0, qv1, (uint16_t)(m01[slot] & 0xffffu), (uint16_t)(m01[slot] >> 16),
+                                        BITS == 8 ? 128.f * s0 : 0.f, BITS == 8 ? 128.f * s1 : 0.f,
+                                        inv_w0, inv_w1, lane);
         __builtin_amdgcn_wave_barrier();   // operand rows are consumed before logits land there
         // the operands of tile + 1 are formed before the products of this tile are issued, so no
         // product waits on the ANDs right in front of it
