@@ -481,16 +481,25 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
           At[s][i] = n16 < gh ? (_Float16)qf[n16 * kD + 32 * s + 8 * kb + i] : (_Float16)0;
-      // matrix step s takes channels 32s + 8kb .. +7 from lane (n16, kb): the four lanes of a token
-      // read 64 contiguous bytes per load, so a cache line is touched by two loads, not four
-      const __half* kt_row = a.k_text + ((size_t)row * a.n_text_cap + txt0) * kD + 8 * kb;
+      // Loads that touch whole cache lines: a wave-wide load covers one 128-byte line of 8 tokens,
+      // lanes n16 < 8 its first 64 bytes (8kb .. +7 of 32 channels), lanes n16 >= 8 the other 64.
+      // Matrix columns n16 and n16 + 8 thus hold the same token with different channels: two
+      // accumulators take the two matching query slices (the other half of each is discarded) and
+      // the halves meet through a rotation by 8 lanes.  Twice the matrix work, which is idle
+      // anyway, for half the cache-line requests.  A 16-token tile is two such 8-token halves.
+      const int tsub = n16 & 7, hsel = n16 >> 3;
+      const __half* kt_row = a.k_text + ((size_t)row * a.n_text_cap + txt0) * kD + 32 * hsel + 8 * kb;
       const int n_tiles = (ntx + 15) / 16;
-      v8h kt[kRingT][4];
+      v8h kt[kRingT][4];                       // [half u][line]: index 2u + line
       auto load_tile = [&](int slot, int tile) {
-        const int tok = min(min(tile, n_tiles - 1) * 16 + n16, ntx - 1);
-        const v8h* src = reinterpret_cast<const v8h*>(kt_row + (size_t)tok * kD);
+        const int t0 = min(tile, n_tiles - 1) * 16 + tsub;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) kt[slot][s] = src[4 * s];
+        for (int u = 0; u < 2; ++u) {
+          const int tok = min(t0 + 8 * u, ntx - 1);
+          const v8h* src = reinterpret_cast<const v8h*>(kt_row + (size_t)tok * kD);
+          kt[slot][2 * u] = src[0];            // channels 32 hsel + 8kb .. of line 0 (channels 0..63)
+          kt[slot][2 * u + 1] = src[8];        // the same of line 1 (channels 64..127)
+        }
       };
 #pragma unroll
       for (int d = 0; d < kRingT; ++d) load_tile(d, tw + d * kTextWaves);
@@ -500,19 +509,27 @@ fused_row_kernel(const FusedArgs a) {
         for (int d = 0; d < kRingT; ++d) {
           const int tile = t + d * kTextWaves;
           if (tile < n_tiles) {
-            v4f c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
-              c = __builtin_amdgcn_mfma_f32_16x16x32_f16(At[s], kt[d][s], c, 0, 0, 0);
-            const int tok = tile * 16 + n16;
-            if (tok < ntx) {     // result rows 4*kb + r are heads; only heads < g exist
+            for (int u = 0; u < 2; ++u) {
+              const v4f z = {0.f, 0.f, 0.f, 0.f};
+              v4f cx = __builtin_amdgcn_mfma_f32_16x16x32_f16(At[0], kt[d][2 * u], z, 0, 0, 0);
+              v4f cy = __builtin_amdgcn_mfma_f32_16x16x32_f16(At[1], kt[d][2 * u], z, 0, 0, 0);
+              cx = __builtin_amdgcn_mfma_f32_16x16x32_f16(At[2], kt[d][2 * u + 1], cx, 0, 0, 0);
+              cy = __builtin_amdgcn_mfma_f32_16x16x32_f16(At[3], kt[d][2 * u + 1], cy, 0, 0, 0);
+              // columns < 8 of cx and columns >= 8 of cy are the valid halves of the same tokens
+              v4f c;
 #pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                const int h = 4 * kb + r;
-                if (h < gh) {
-                  const float sv = c[r] * a.softmax_scale;
-                  logits[h * a.stride + nv + tok] = sv;
-                  tmax[r] = fmaxf(tmax[r], sv);
+              for (int r = 0; r < 4; ++r) c[r] = cx[r] + dpp_f32<0x128>(cy[r]);     // row_ror 8
+              const int tok = tile * 16 + 8 * u + tsub;
+              if (hsel == 0 && tok < ntx) {     // result rows 4*kb + r are heads; only heads < g exist
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                  const int h = 4 * kb + r;
+                  if (h < gh) {
+                    const float sv = c[r] * a.softmax_scale;
+                    logits[h * a.stride + nv + tok] = sv;
+                    tmax[r] = fmaxf(tmax[r], sv);
+                  }
                 }
               }
             }
