@@ -46,7 +46,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list")
     ap.add_argument("--bits", type=int, default=1)
-    ap.add_argument("--group", type=int, default=128)
+    ap.add_argument("--group", type=int, default=128,
+                    help="tokens per key group (32, 64, 128); 0 = statistics over the whole "
+                         "sequence, one pair per channel (the paper's scheme as printed)")
     ap.add_argument("--v-axis", choices=["token", "channel"], default="token",
                     help="value statistics: per token (the benchmark's layout) or per channel over "
                          "groups of tokens (the paper's own choice)")
@@ -133,13 +135,14 @@ def main() -> int:
         return 0
     # --group is the key group (tokens); token-wise values keep one group per token, channel-wise
     # values use the same token group as the keys
-    v_group = args.group if args.v_axis == "channel" else w.head_dim
+    k_group = args.group if args.group > 0 else w.n_vis
+    v_group = k_group if args.v_axis == "channel" else w.head_dim
     lay = cq.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_vis, args.bits,
                          cq.CQ_AXIS_CHANNEL,
                          cq.CQ_AXIS_CHANNEL if args.v_axis == "channel" else cq.CQ_AXIS_TOKEN,
-                         args.group, v_group)
+                         k_group, v_group)
     calib = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
-    bytes_call, per_vis, per_text = algorithmic_bytes(w, args.bits, args.group, v_group)
+    bytes_call, per_vis, per_text = algorithmic_bytes(w, args.bits, k_group, v_group)
 
     # ---- resident inputs: several independent sets so that no call finds its cache warm
     n_sets = int(min(32, max(3, math.ceil(800e6 / bytes_call))))
@@ -242,7 +245,7 @@ def main() -> int:
     if not args.no_fp16_baseline:
         n_all = w.n_vis + w.n_text
         lay16 = cq.make_layout(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, 0, args.bits,
-                               cq.CQ_AXIS_CHANNEL, cq.CQ_AXIS_TOKEN, args.group, args.group)
+                               cq.CQ_AXIS_CHANNEL, cq.CQ_AXIS_TOKEN, 128, 128)
         gen = torch.Generator(device=dev)
         gen.manual_seed(w.seed + 17)
         shape16 = (w.batch, w.n_kv_heads, n_all, w.head_dim)
@@ -293,7 +296,9 @@ def main() -> int:
 
     # quantizer figures (bytes read + written per call)
     rows = w.batch * w.n_kv_heads
-    q_bytes = rows * w.n_vis * (2 * w.head_dim * 2) + rows * w.n_vis * (per_vis)
+    # a tensor with whole-sequence statistics is read twice (extrema pass, then codes)
+    q_reads = (2 if k_group == w.n_vis else 1) + (2 if v_group == w.n_vis and args.v_axis == "channel" else 1)
+    q_bytes = rows * w.n_vis * (q_reads * w.head_dim * 2) + rows * w.n_vis * (per_vis)
     q_ms = sorted(quant_ms)[len(quant_ms) // 2]
 
     # which kernel ran: forcing the tuned path fails loudly when the layout would fall back
@@ -305,7 +310,7 @@ def main() -> int:
     except cq.CqError:
         fused = False
     cq.cq_set_kernel_path(prev_path)
-    kernel_name = ("fused_row_kernel<%d> (the call's only launch)" % (args.group // 16) if fused
+    kernel_name = ("fused_row_kernel<%d> (the call's only launch)" % (min(k_group, 128) // 16) if fused
                    else "scores_kernel + pv_kernel + combine_kernel (all launches of one call)")
     traffic = None
     if (fused and args.config == 2 and args.bits == 1 and args.group == 128 and not args.batch
@@ -336,7 +341,7 @@ def main() -> int:
         "config": {"workload": "configs[%d] %s" % (args.config, w.name), "batch": w.batch,
                    "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_vis": w.n_vis, "n_text": w.n_text, "bits": args.bits,
-                   "k_group": args.group, "v_group": v_group, "v_axis": args.v_axis,
+                   "k_group": k_group, "v_group": v_group, "v_axis": args.v_axis,
                    "calib": "dynamic tau=(1,2)",
                    "kernel_path": args.path, "input_sets": n_sets},
         "launch": args.launch,
@@ -353,7 +358,7 @@ def main() -> int:
                      "bytes_per_visual_token_per_kv_head": per_vis,
                      "bytes_per_text_token_per_kv_head": per_text},
         "fp16_baseline": fp16_baseline,
-        "quantizer": {"ms": q_ms, "bytes_read_plus_written": q_bytes,
+        "quantizer": {"ms": q_ms, "bytes_read_plus_written": q_bytes, "reads_of_k_plus_v": q_reads,
                       "GB/s": q_bytes / (q_ms * 1e-3) / 1e9,
                       "frac_of_hbm_peak": q_bytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                       "tokens_per_s": rows * w.n_vis / (q_ms * 1e-3)},
@@ -365,8 +370,9 @@ def main() -> int:
     if not args.no_cpu_baseline:
         # the oracle as it stands, on one batch item of the same workload (sample of the call)
         from oracle import cq_oracle as O
-        kq = O.quantize_tensor(sample0["k"].numpy(), args.bits, O.AXIS_CHANNEL, args.group)
-        vq = O.quantize_tensor(sample0["v"].numpy(), args.bits, O.AXIS_TOKEN, args.group)
+        kq = O.quantize_tensor(sample0["k"].numpy(), args.bits, O.AXIS_CHANNEL, k_group)
+        vq = O.quantize_tensor(sample0["v"].numpy(), args.bits,
+                               O.AXIS_CHANNEL if args.v_axis == "channel" else O.AXIS_TOKEN, v_group)
         n_rep, t_used = 0, 0.0
         while t_used < 12.0 and n_rep < 400:
             c0 = time.perf_counter()

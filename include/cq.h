@@ -91,7 +91,10 @@ typedef struct {
  * code = round((x - min) * (2^b-1) / (max - min)) evaluated exactly with ties to
  * even; a constant group gives codes 0 and scale 0.  Either of (k_f16, k_out) or
  * (v_f16, v_out) may be NULL as a pair to quantize only the other tensor.
- * n_vis == 0 is a successful no-op.
+ * n_vis == 0 is a successful no-op.  The output buffers may hold intermediate
+ * results until the call's work on `stream` has completed (whole-sequence
+ * statistics keep partial extrema in `codes` between their passes); no other
+ * memory is touched and nothing is allocated.
  */
 int cq_quantize_kv(const cq_layout_t *layout, const void *k_f16, const void *v_f16,
                    const cq_qtensor_t *k_out, const cq_qtensor_t *v_out, void *stream);

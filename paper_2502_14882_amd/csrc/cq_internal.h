@@ -62,8 +62,8 @@ hipError_t launch_decode_generic(const DecodeShape& s, const void* q, const cq_q
                                  const Calib& calib, float softmax_scale, void* out,
                                  float* workspace, const Workspace& wl, hipStream_t stream);
 
-// Register-resident tile quantizer for head_dim 128, b in {1,2}, groups of 32/64/128 and
-// n_vis a multiple of 128.
+// Register-resident tile quantizer for head_dim 128, b in {1,2,4,8}, n_vis a multiple of 128,
+// groups of 32/64/128 or (channel axis) the whole sequence, which adds an extrema pass.
 bool quantize_tuned_supported(int n_vis, int d, int bits, int axis, int group);
 hipError_t launch_quantize_tuned(const void* x_f16, const cq_qtensor_t& out, int rows, int n_vis,
                                  int bits, int axis, int group, hipStream_t stream);

@@ -78,8 +78,14 @@ struct FusedArgs {
   const uint32_t* v_codes; const float* v_scale; const uint16_t* v_min;
   const __half* k_text; const __half* v_text;
   __half* out;
-  int Hq, Hkv, g, n_vis, n_text, n_text_cap, k_group;
-  int v_group;       // channel-wise values: tokens per value group (64 or 128)
+  int Hq, Hkv, g, n_vis, n_text, n_text_cap;
+  int k_group;       // tokens that are processed as one key group (32, 64 or 128)
+  int v_group;       // channel-wise values: tokens processed as one value group (64 or 128)
+  // Parameters (scale, min) of channel-wise tensors: elements per row, and elements between two
+  // consecutive processing groups.  Statistics over the whole sequence (Sec. 3.1 as printed: one
+  // pair per channel) are one parameter group per row that every processing group of 128
+  // tokens reads again: pstride = 0.
+  int k_prow, k_pstride, v_prow, v_pstride;
   int unit;          // chunk boundaries are multiples of unit key groups
   int stride;        // floats between the logit rows of two heads in LDS
   int mode, n_chunks, nhb;   // kMode*, chunks per row, blocks of 4 query heads per KV head
@@ -239,9 +245,12 @@ __device__ inline int code_in_word(int y, int v) {
 // TILES = 16-token tiles per key group (k_group / 16); BITS = code width (1, 2, 4 or 8); VCH = values
 // quantized channel-wise over groups of tokens (Sec. 3.1, the paper's own choice) instead of
 // token-wise.
-template <int TILES, int BITS, bool VCH>
+// KW = key statistics over the whole sequence: one parameter group per row, so the query operand,
+// its shift and the additive term are formed once per wave instead of once per 128 tokens.
+template <int TILES, int BITS, bool VCH, bool KW = false>
 __global__ void __launch_bounds__(kThreads)
 fused_row_kernel(const FusedArgs a) {
+  static_assert(!KW || TILES == 8, "whole-sequence keys are processed 128 tokens at a time");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // workgroup = (row = b * Hkv + kvh, block of 4 query heads, chunk of the row's tokens)
   // Workgroups are handed to the 8 XCDs round-robin.  With two head blocks per KV head, the two
@@ -292,8 +301,8 @@ fused_row_kernel(const FusedArgs a) {
   // ---- phase 0: query to LDS and max |q| per head.  The fixed-point shifts and the additive
   // post-scaling term q . min_t are formed on the fly in phases 1 and 2 from the scales and minima
   // that the streaming loads bring in anyway, so every parameter is read exactly once.
-  const float* ks_row = a.k_scale + ((size_t)row * (a.n_vis / a.k_group) + ga) * kD;
-  const uint16_t* km_row = a.k_min + ((size_t)row * (a.n_vis / a.k_group) + ga) * kD;
+  const float* ks_row = a.k_scale + (size_t)row * a.k_prow + (size_t)ga * a.k_pstride;
+  const uint16_t* km_row = a.k_min + (size_t)row * a.k_prow + (size_t)ga * a.k_pstride;
   const float* vs_row = a.v_scale + (size_t)row * a.n_vis + vis0;
   const uint16_t* vm_row = a.v_min + (size_t)row * a.n_vis + vis0;
   if (tid < kHeads * kD) {
@@ -354,7 +363,7 @@ fused_row_kernel(const FusedArgs a) {
       float* lrow = logits + (size_t)hres * a.stride + n16;
       // with 128-token groups the operand rows of a group are staged in the group's own logit
       // slots (2 KB, not yet written); smaller groups use the wave's staging buffer
-      constexpr bool kInPlace = (TILES == 8);
+      constexpr bool kInPlace = (TILES == 8) && !KW;
       const int pitch = kInPlace ? a.stride * 4 : 512;
       const int x_wr0 = kb * pitch + wr0 * 16, x_wr1 = kb * pitch + wr1 * 16;
       const int x_rd = kb * pitch + (n16 >> 1) * 16 + (n16 & 1) * 8;
@@ -372,10 +381,14 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
           for (int e = 0; e < BITS; ++e)
             w[slot][i][e] = kc_lane[((size_t)tc * TILES + i) * (64 * BITS) + e];
-        s01[slot] = *reinterpret_cast<const v2f*>(ks_row + (size_t)tc * kD + wc0);
-        m01[slot] = *reinterpret_cast<const uint32_t*>(km_row + (size_t)tc * kD + wc0);
+        if constexpr (!KW) {
+          s01[slot] = *reinterpret_cast<const v2f*>(ks_row + (size_t)tc * a.k_pstride + wc0);
+          m01[slot] = *reinterpret_cast<const uint32_t*>(km_row + (size_t)tc * a.k_pstride + wc0);
+        }
       };
-      auto do_group = [&](int slot, int t) {
+      // query operand of the key group whose parameters sit in ring slot `slot`, staged at xb
+      auto build_operand = [&](int slot, uint8_t* xb, v4i& A0, v4i& A1, float& bias_h,
+                               float& inv_f, float& inv_f16) {
         // |q'| <= max|q| * (largest scale of the group): a bound, good to a few bits, that costs
         // one wave-wide maximum instead of a pass over all scales
         const float s0 = s01[slot][0], s1 = s01[slot][1];
@@ -388,8 +401,8 @@ fused_row_kernel(const FusedArgs a) {
           x0[h] = product_digits(qv0[h], s0f);
           x1[h] = product_digits(qv1[h], s1f);
         }
-        const float inv_f = ldexpf(1.f, -F), inv_f16 = ldexpf(1.f, 16 - F);
-        uint8_t* xb = kInPlace ? lbytes + (size_t)t * (TILES * 16 * 4) : stage;
+        inv_f = ldexpf(1.f, -F);
+        inv_f16 = ldexpf(1.f, 16 - F);
         __builtin_amdgcn_wave_barrier();
         *reinterpret_cast<v4i*>(xb + x_wr0) = x0;
         *reinterpret_cast<v4i*>(xb + x_wr1) = x1;
@@ -398,12 +411,21 @@ fused_row_kernel(const FusedArgs a) {
         const uint8_t* xr = xb + x_rd;
         const v2i r00 = lds_read_tr8(xr), r01 = lds_read_tr8(xr + 128);
         const v2i r10 = lds_read_tr8(xr + 256), r11 = lds_read_tr8(xr + 384);
-        const v4i A0 = {r00[0], r00[1], r01[0], r01[1]};
-        const v4i A1 = {r10[0], r10[1], r11[0], r11[1]};
-        const float bias_h = group_bias(qv0, qv1, (uint16_t)(m01[slot] & 0xffffu), (uint16_t)(m01[slot] >> 16),
+        A0 = (v4i){r00[0], r00[1], r01[0], r01[1]};
+        A1 = (v4i){r10[0], r10[1], r11[0], r11[1]};
+        bias_h = group_bias(qv0, qv1, (uint16_t)(m01[slot] & 0xffffu), (uint16_t)(m01[slot] >> 16),
                                         BITS == 8 ? 128.f * s0 : 0.f, BITS == 8 ? 128.f * s1 : 0.f,
                                         inv_w0, inv_w1, lane);
         __builtin_amdgcn_wave_barrier();   // operand rows are consumed before logits land there
+      };
+      v4i A0w = {0, 0, 0, 0}, A1w = {0, 0, 0, 0};
+      float bias_w = 0.f, inv_f_w = 0.f, inv_f16_w = 0.f;
+      auto do_group = [&](int slot, int t) {
+        v4i A0 = A0w, A1 = A1w;
+        float bias_h = bias_w, inv_f = inv_f_w, inv_f16 = inv_f16_w;
+        if constexpr (!KW)
+          build_operand(slot, kInPlace ? lbytes + (size_t)t * (TILES * 16 * 4) : stage,
+                        A0, A1, bias_h, inv_f, inv_f16);
         // the operands of tile + 1 are formed before the products of this tile are issued, so no
         // product waits on the ANDs right in front of it
         auto expand = [&](int tile, v4i& B0, v4i& B1) {
@@ -442,9 +464,18 @@ fused_row_kernel(const FusedArgs a) {
           finish_tile(tile + 1, cb);
         }
       };
+      if constexpr (KW) {                           // the row's parameters first, then the codes
+        s01[0] = *reinterpret_cast<const v2f*>(ks_row + wc0);
+        m01[0] = *reinterpret_cast<const uint32_t*>(km_row + wc0);
+        pin_order();
+      }
 #pragma unroll
       for (int d = 0; d < kRK; ++d) load_group(d, wave + d * kVisWaves);
       pin_order();
+      if constexpr (KW) {
+        build_operand(0, stage, A0w, A1w, bias_w, inv_f_w, inv_f16_w);
+        pin_order();
+      }
       int t = wave;
       for (; t + (kRK - 1) * kVisWaves < n_groups; t += kRK * kVisWaves) {
 #pragma unroll
@@ -630,12 +661,12 @@ fused_row_kernel(const FusedArgs a) {
       const int n_vg = nv / VG;
       const int n_my = n_vg > wave ? ((n_vg - wave + kVisWaves - 1) / kVisWaves) << tsh : 0;
       const uint32_t* vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS);
-      const size_t g0 = (size_t)row * (a.n_vis / VG) + vis0 / VG;
+      const size_t g0 = (size_t)row * a.v_prow + (size_t)(vis0 / VG) * a.v_pstride;
       // the lane's result columns are code byte n16: 8 (b = 1) or 2 x 4 (b = 2) consecutive channels
       const int c_lo = BITS == 1 ? 32 * (n16 >> 2) + 24 - 8 * (n16 & 3) : 16 * (n16 >> 2) + 12 - 4 * (n16 & 3);
       const int c_hi = BITS == 1 ? c_lo + 4 : c_lo + 64;
-      const float* vsc = a.v_scale + g0 * kD;
-      const uint16_t* vmn = a.v_min + g0 * kD;
+      const float* vsc = a.v_scale + g0;
+      const uint16_t* vmn = a.v_min + g0;
       const int x_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;
       const int x_rd = (kb * a.stride) * 4 + (n16 >> 1) * 16 + (n16 & 1) * 8;
       const int v_rd = (kb * 16 + (n16 >> 1)) * (16 * BITS) + (n16 & 1) * 8;
@@ -654,10 +685,10 @@ fused_row_kernel(const FusedArgs a) {
       v2i gmn[2];
       auto load_group = [&](int gi) {         // scales and minima of the wave's gi-th group
         const int grp = min(wave + gi * kVisWaves, n_vg - 1);
-        gsc[0] = *reinterpret_cast<const v4f*>(vsc + (size_t)grp * kD + c_lo);
-        gsc[1] = *reinterpret_cast<const v4f*>(vsc + (size_t)grp * kD + c_hi);
-        gmn[0] = *reinterpret_cast<const v2i*>(vmn + (size_t)grp * kD + c_lo);
-        gmn[1] = *reinterpret_cast<const v2i*>(vmn + (size_t)grp * kD + c_hi);
+        gsc[0] = *reinterpret_cast<const v4f*>(vsc + (size_t)grp * a.v_pstride + c_lo);
+        gsc[1] = *reinterpret_cast<const v4f*>(vsc + (size_t)grp * a.v_pstride + c_hi);
+        gmn[0] = *reinterpret_cast<const v2i*>(vmn + (size_t)grp * a.v_pstride + c_lo);
+        gmn[1] = *reinterpret_cast<const v2i*>(vmn + (size_t)grp * a.v_pstride + c_hi);
       };
       auto prep_tile = [&](int slot, int k, int buf) {
         const int jt = tile_start(k);
@@ -1144,6 +1175,18 @@ long long device_cu_count() {
   return v;
 }
 
+// Channel-wise statistics over the whole sequence (group = n_vis, the scheme of Sec. 3.1 as
+// printed) run as processing groups of 128 tokens that share the row's one parameter group.
+// Returns the shape the kernel works on.
+DecodeShape processing_shape(const DecodeShape& s, bool* k_whole, bool* v_whole) {
+  DecodeShape e = s;
+  *k_whole = s.k_axis == CQ_AXIS_CHANNEL && s.k_group == s.n_vis && s.n_vis > 128 && s.n_vis % 128 == 0;
+  *v_whole = s.v_axis == CQ_AXIS_CHANNEL && s.v_group == s.n_vis && s.n_vis > 128 && s.n_vis % 128 == 0;
+  if (*k_whole) e.k_group = 128;
+  if (*v_whole) e.v_group = 128;
+  return e;
+}
+
 // Chunks of a split row start at multiples of `unit` key groups: whole 64-token value tiles and,
 // with channel-wise values, whole value groups.
 int chunk_unit(const DecodeShape& s) {
@@ -1172,8 +1215,10 @@ void chunk_extent(const DecodeShape& s, int n_chunks, int* nv_max, int* nt_max) 
   }
 }
 
-FusedPlan make_plan(const DecodeShape& s, size_t workspace_bytes) {
+FusedPlan make_plan(const DecodeShape& shape, size_t workspace_bytes) {
   FusedPlan p;
+  bool k_whole, v_whole;
+  const DecodeShape s = processing_shape(shape, &k_whole, &v_whole);
   if (s.d != kD || (s.bits != 1 && s.bits != 2 && s.bits != 4 && s.bits != 8)) return p;
   if (s.bits > 2 && s.v_axis != CQ_AXIS_TOKEN) return p;     // wide codes: token-wise values only
   if (s.k_axis != CQ_AXIS_CHANNEL) return p;
@@ -1248,12 +1293,14 @@ bool fused_supported(const DecodeShape& s, size_t workspace_bytes) {
   return make_plan(s, workspace_bytes).ok;
 }
 
-hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
+hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq_qtensor_t& k,
                                const cq_qtensor_t& v, const void* k_text, const void* v_text,
                                const Calib& calib, float softmax_scale, void* out,
                                float* workspace, size_t workspace_bytes, hipStream_t stream) {
-  const FusedPlan plan = make_plan(s, workspace_bytes);
+  const FusedPlan plan = make_plan(shape, workspace_bytes);
   if (!plan.ok) return hipErrorInvalidValue;
+  bool k_whole, v_whole;
+  const DecodeShape s = processing_shape(shape, &k_whole, &v_whole);
   FusedArgs a;
   a.q = static_cast<const __half*>(q);
   a.k_codes = k.codes; a.k_scale = k.scale; a.k_min = k.min;
@@ -1264,6 +1311,13 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
   a.Hq = s.Hq; a.Hkv = s.Hkv; a.g = s.g; a.n_vis = s.n_vis; a.n_text = s.n_text;
   a.n_text_cap = s.n_text_cap; a.k_group = s.k_group;
   a.v_group = s.v_group; a.unit = chunk_unit(s);
+  a.k_prow = k_whole ? kD : s.n_vis / s.k_group * kD;
+  a.k_pstride = k_whole ? 0 : kD;
+  a.v_prow = a.v_pstride = 0;
+  if (s.v_axis == CQ_AXIS_CHANNEL) {
+    a.v_prow = v_whole ? kD : s.n_vis / s.v_group * kD;
+    a.v_pstride = v_whole ? 0 : kD;
+  }
   a.calib_mode = calib.mode; a.tau1 = calib.tau1; a.tau2 = calib.tau2;
   a.gamma = calib.gamma; a.delta = calib.delta; a.softmax_scale = softmax_scale;
   a.stride = plan.stride;
@@ -1277,7 +1331,17 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
   void (*kern)(const FusedArgs) = nullptr;
   int slot = 0;
   const bool vch = s.v_axis == CQ_AXIS_CHANNEL;
-  switch ((s.k_group * 4 + s.bits) * 2 + (vch ? 1 : 0)) {
+  if (k_whole) {
+    switch (s.bits * 2 + (vch ? 1 : 0)) {
+      case 1 * 2: kern = fused_row_kernel<8, 1, false, true>; slot = 18; break;
+      case 2 * 2: kern = fused_row_kernel<8, 2, false, true>; slot = 19; break;
+      case 4 * 2: kern = fused_row_kernel<8, 4, false, true>; slot = 20; break;
+      case 8 * 2: kern = fused_row_kernel<8, 8, false, true>; slot = 21; break;
+      case 1 * 2 + 1: kern = fused_row_kernel<8, 1, true, true>; slot = 22; break;
+      case 2 * 2 + 1: kern = fused_row_kernel<8, 2, true, true>; slot = 23; break;
+      default: return hipErrorInvalidValue;
+    }
+  } else switch ((s.k_group * 4 + s.bits) * 2 + (vch ? 1 : 0)) {
     case (32 * 4 + 1) * 2: kern = fused_row_kernel<2, 1, false>; slot = 0; break;
     case (64 * 4 + 1) * 2: kern = fused_row_kernel<4, 1, false>; slot = 1; break;
     case (128 * 4 + 1) * 2: kern = fused_row_kernel<8, 1, false>; slot = 2; break;
@@ -1300,7 +1364,7 @@ hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qte
   }
   // the kernel's dynamic LDS limit is raised once per (device, kernel) and only ever grows;
   // concurrent callers may both raise it, which is harmless
-  static std::atomic<size_t> configured[kMaxDevices][18];
+  static std::atomic<size_t> configured[kMaxDevices][24];
   int dev = 0;
   hipError_t de = hipGetDevice(&dev);
   if (de != hipSuccess) return de;

@@ -1,4 +1,5 @@
-// Tuned quantizer for head_dim 128, b in {1, 2, 4, 8}, groups of 32/64/128 (gfx950).
+// Tuned quantizer for head_dim 128, b in {1, 2, 4, 8}, groups of 32/64/128 or, channel-wise, the
+// whole sequence (gfx950).
 //
 // One 256-thread block quantizes a tile of 128 tokens x 128 channels (32 KB of fp16), read once
 // with 16-byte loads and kept in registers:
@@ -15,6 +16,12 @@
 //   b in {4, 8} (too many thresholds): step 2 stores min and (2^b-1)/(max-min) per group, step 3
 //   evaluates the quantize equation per element in fp64 with that reciprocal and settles the
 //   rounding exactly (see exact_code); a lane's 8 channels fill one word (b = 4) or two (b = 8).
+// Channel-wise statistics over the whole sequence (group = n_vis: one pair per channel, Sec. 3.1
+// as printed) take a pass of their own: row_extrema_kernel leaves kSplits partial (min, max)
+// pairs per channel in the code words of the row's LAST tile (the caller's output buffer: no
+// other memory is needed), the tile kernel reduces them instead of computing tile statistics,
+// and the last tile of every row is quantized by a second launch, after all other tiles have
+// read the partials it overwrites.
 // Results are bit-identical to evaluating the quantize equation element by element in fp64.
 #include <hip/hip_fp16.h>
 
@@ -31,6 +38,8 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 constexpr int kD = 128;
 constexpr int kTile = 128;       // tokens per block
 constexpr int kThreads = 256;
+constexpr int kSplits = 4;       // partial extrema per row: 4 x 128 x (min, max) fp16 = 2 KB = one tile's
+                                 // code words at b = 1
 
 // ---- fp16 bit patterns as an ordered set
 __device__ inline uint16_t h_key(uint16_t u) { return (u & 0x8000u) ? (uint16_t)~u : (uint16_t)(u | 0x8000u); }
@@ -125,15 +134,85 @@ struct QArgs {
   uint32_t* codes;
   float* scale;
   uint16_t* minv;
+  // whole-sequence statistics only: tiles per row, and the tiles of every row that this launch
+  // covers (tile_first .. tile_first + tiles_launch - 1)
+  int tiles_row, tile_first, tiles_launch;
 };
 
-// AXIS: CQ_AXIS_CHANNEL (GROUP tokens per group) or CQ_AXIS_TOKEN (GROUP channels per group)
+// Partial extrema of a row's split sp live at [(sp * 2 + {0: min, 1: max}) * kD + channel], fp16,
+// in the code words of the row's last tile.
+__device__ inline _Float16* row_partials(const QArgs& a, int row, int words_per_token) {
+  const size_t last_tok = ((size_t)row * a.tiles_row + (a.tiles_row - 1)) * kTile;
+  return reinterpret_cast<_Float16*>(a.codes + last_tok * words_per_token);
+}
+
+// First pass of whole-sequence statistics: block (row, sp) scans its share of the row's tiles.
+template <int BITS>
+__global__ void __launch_bounds__(kThreads)
+row_extrema_kernel(const QArgs a) {
+  __shared__ __align__(16) _Float16 s_part[2][4][kD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c8 = lane & 15, ts = lane >> 4;
+  const int row = blockIdx.x / kSplits, sp = blockIdx.x % kSplits;
+  const int ta = a.tiles_row * sp / kSplits, tb = a.tiles_row * (sp + 1) / kSplits;
+  const v8h* src = reinterpret_cast<const v8h*>(a.x) +
+                   ((size_t)row * a.tiles_row * kTile + 32 * wave + ts) * (kD / 8) + c8;
+  const _Float16 inf = __builtin_bit_cast(_Float16, (uint16_t)0x7c00u);
+  v8h mn = {inf, inf, inf, inf, inf, inf, inf, inf};        // an empty share leaves the neutral pair
+  v8h mx = -mn;
+  for (int t = ta; t < tb; ++t) {
+    v8h x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = src[((size_t)t * kTile + 4 * i) * (kD / 8)];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      mn = __builtin_elementwise_min(mn, x[i]);
+      mx = __builtin_elementwise_max(mx, x[i]);
+    }
+  }
+  v4u mnu = __builtin_bit_cast(v4u, mn), mxu = __builtin_bit_cast(v4u, mx);
+#pragma unroll
+  for (int o = 16; o <= 32; o <<= 1) {
+    v4u on, ox;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      on[r] = __shfl_xor(mnu[r], o);
+      ox[r] = __shfl_xor(mxu[r], o);
+    }
+    mn = __builtin_elementwise_min(mn, __builtin_bit_cast(v8h, on));
+    mx = __builtin_elementwise_max(mx, __builtin_bit_cast(v8h, ox));
+    mnu = __builtin_bit_cast(v4u, mn);
+    mxu = __builtin_bit_cast(v4u, mx);
+  }
+  if (ts == 0) {
+    *reinterpret_cast<v8h*>(&s_part[0][wave][c8 * 8]) = mn;
+    *reinterpret_cast<v8h*>(&s_part[1][wave][c8 * 8]) = mx;
+  }
+  __syncthreads();
+  if (tid < kD) {
+    _Float16 lo = s_part[0][0][tid], hi = s_part[1][0][tid];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      lo = (_Float16)fminf((float)lo, (float)s_part[0][w][tid]);
+      hi = (_Float16)fmaxf((float)hi, (float)s_part[1][w][tid]);
+    }
+    _Float16* part = row_partials(a, row, kD * BITS / 32);
+    part[(sp * 2 + 0) * kD + tid] = lo;
+    part[(sp * 2 + 1) * kD + tid] = hi;
+  }
+}
+
+// AXIS: CQ_AXIS_CHANNEL (GROUP tokens per group; GROUP = 0: the whole sequence, extrema from
+// row_extrema_kernel) or CQ_AXIS_TOKEN (GROUP channels per group)
 template <int AXIS, int BITS, int GROUP>
 __global__ void __launch_bounds__(kThreads)
 quantize_tile_kernel(const QArgs a) {
   constexpr int L = (1 << BITS) - 1;
   constexpr int kWords = kD * BITS / 32;                  // words per token
-  constexpr int NG = AXIS == CQ_AXIS_CHANNEL ? kTile / GROUP : kD / GROUP;   // groups per tile / token
+  constexpr bool kWhole = GROUP == 0;
+  static_assert(!kWhole || AXIS == CQ_AXIS_CHANNEL, "whole-sequence statistics are channel-wise");
+  constexpr int kG = kWhole ? kTile : GROUP;              // a tile of a whole row is one group
+  constexpr int NG = AXIS == CQ_AXIS_CHANNEL ? kTile / kG : kD / kG;         // groups per tile / token
   __shared__ __align__(16) _Float16 s_part[2][4][kD];     // channel axis: per-wave min, max
   __shared__ __align__(16) _Float16 s_stat[kTile][4][2];  // token axis: min, max per (token, group)
   constexpr bool kWide = BITS > 2;                        // per-element arithmetic instead of thresholds
@@ -144,7 +223,10 @@ quantize_tile_kernel(const QArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c8 = lane & 15, ts = lane >> 4;
-  const size_t tok0 = (size_t)blockIdx.x * kTile;         // tiles never straddle rows (n_vis % 128 == 0)
+  // tiles never straddle rows (n_vis % 128 == 0)
+  const int wrow = kWhole ? blockIdx.x / a.tiles_launch : 0;
+  const int wtile = kWhole ? a.tile_first + blockIdx.x % a.tiles_launch : 0;
+  const size_t tok0 = kWhole ? ((size_t)wrow * a.tiles_row + wtile) * kTile : (size_t)blockIdx.x * kTile;
   const v8h* src = reinterpret_cast<const v8h*>(a.x) + (tok0 + 32 * wave + ts) * (kD / 8) + c8;
 
   v8h x[8];
@@ -152,7 +234,36 @@ quantize_tile_kernel(const QArgs a) {
   for (int i = 0; i < 8; ++i)                                              // token 32w + 4i + ts
     x[i] = __builtin_nontemporal_load(src + (size_t)i * 4 * (kD / 8));   // read exactly once
 
-  if constexpr (AXIS == CQ_AXIS_CHANNEL) {
+  if constexpr (kWhole) {
+    // ---- 1 + 2. the row's extrema from the partials of the first pass; parameters and thresholds
+    if (tid < kD) {
+      const int c = tid;
+      const _Float16* part = row_partials(a, wrow, kWords);
+      _Float16 lo = part[c], hi = part[kD + c];
+#pragma unroll
+      for (int sp = 1; sp < kSplits; ++sp) {
+        lo = (_Float16)fminf((float)lo, (float)part[(sp * 2 + 0) * kD + c]);
+        hi = (_Float16)fmaxf((float)hi, (float)part[(sp * 2 + 1) * kD + c]);
+      }
+      const uint16_t mbits = canonical_zero(__builtin_bit_cast(uint16_t, lo));
+      const double alpha = h_to_double(mbits);
+      const double D = ((double)(float)hi - alpha) + 0.0;
+      if (wtile == a.tiles_row - 1) {          // one block per row stores the parameters
+        a.scale[(size_t)wrow * kD + c] = (float)(D / (double)L);
+        a.minv[(size_t)wrow * kD + c] = mbits;
+      }
+      if constexpr (kWide) {
+        s_alpha[c] = __builtin_bit_cast(_Float16, mbits);
+        s_rinv[c] = D > 0.0 ? (double)L / D : 0.0;
+      } else {
+#pragma unroll
+        for (int k = 1; k <= L; ++k)
+          s_thr[(k - 1) * kD + c] = __builtin_bit_cast(_Float16, threshold_bits(alpha, D, k, L));
+      }
+    }
+    __syncthreads();   // in the row's last tile this also orders the reads above before the
+                       // block's own code words, which replace the partials
+  } else if constexpr (AXIS == CQ_AXIS_CHANNEL) {
     // ---- 1. per-channel extrema over the wave's 32 tokens
     v8h mn = x[0], mx = x[0];
 #pragma unroll
@@ -206,8 +317,10 @@ quantize_tile_kernel(const QArgs a) {
       }
     }
     __syncthreads();
+  }
+  if constexpr (AXIS == CQ_AXIS_CHANNEL) {
     // ---- 3. codes
-    const int g = (32 * wave) / GROUP;
+    const int g = (32 * wave) / kG;
     if constexpr (kWide) {
       double al[8], ri[8];
 #pragma unroll
@@ -348,21 +461,49 @@ hipError_t launch_group(int group, const QArgs& a, unsigned blocks, hipStream_t 
   return hipGetLastError();
 }
 
+// whole-sequence statistics: extrema pass, all tiles but the last of every row, the last tiles
+template <int BITS>
+hipError_t launch_whole(QArgs a, unsigned rows, hipStream_t stream) {
+  row_extrema_kernel<BITS><<<dim3(rows * kSplits), dim3(kThreads), 0, stream>>>(a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  a.tile_first = 0;
+  a.tiles_launch = a.tiles_row - 1;
+  quantize_tile_kernel<CQ_AXIS_CHANNEL, BITS, 0>
+      <<<dim3(rows * (unsigned)a.tiles_launch), dim3(kThreads), 0, stream>>>(a);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  a.tile_first = a.tiles_row - 1;
+  a.tiles_launch = 1;
+  quantize_tile_kernel<CQ_AXIS_CHANNEL, BITS, 0><<<dim3(rows), dim3(kThreads), 0, stream>>>(a);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 bool quantize_tuned_supported(int n_vis, int d, int bits, int axis, int group) {
   if (d != kD || (bits != 1 && bits != 2 && bits != 4 && bits != 8)) return false;
-  if (group != 32 && group != 64 && group != 128) return false;
   if (axis != CQ_AXIS_CHANNEL && axis != CQ_AXIS_TOKEN) return false;
-  return n_vis > 0 && n_vis % kTile == 0;
+  if (n_vis <= 0 || n_vis % kTile != 0) return false;
+  if (axis == CQ_AXIS_CHANNEL && group == n_vis && n_vis > kTile) return true;   // whole sequence
+  return group == 32 || group == 64 || group == 128;
 }
 
 hipError_t launch_quantize_tuned(const void* x_f16, const cq_qtensor_t& out, int rows, int n_vis,
                                  int bits, int axis, int group, hipStream_t stream) {
   const size_t blocks = (size_t)rows * (size_t)(n_vis / kTile);
   if (blocks > 0x7fffffffu) return hipErrorInvalidConfiguration;
-  const QArgs a{static_cast<const __half*>(x_f16), out.codes, out.scale, out.min};
+  const QArgs a{static_cast<const __half*>(x_f16), out.codes, out.scale, out.min, n_vis / kTile, 0, 0};
   const unsigned nb = (unsigned)blocks;
+  if (axis == CQ_AXIS_CHANNEL && group == n_vis && n_vis > kTile) {
+    switch (bits) {
+      case 1: return launch_whole<1>(a, (unsigned)rows, stream);
+      case 2: return launch_whole<2>(a, (unsigned)rows, stream);
+      case 4: return launch_whole<4>(a, (unsigned)rows, stream);
+      case 8: return launch_whole<8>(a, (unsigned)rows, stream);
+    }
+    return hipErrorInvalidValue;
+  }
   if (axis == CQ_AXIS_CHANNEL) {
     switch (bits) {
       case 1: return launch_group<CQ_AXIS_CHANNEL, 1>(group, a, nb, stream);

@@ -262,6 +262,33 @@ def test_tuned_channelwise_values(kernel_path, bits, kg, vg):
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
+@pytest.mark.parametrize("v_whole", [False, True])
+def test_tuned_whole_sequence_statistics(kernel_path, bits, v_whole, monkeypatch):
+    """Sec. 3.1 as printed: one (scale, min) pair per channel over ALL visual tokens, for keys and
+    (v_whole) for values too, on the tuned kernels; whole rows and rows split into chunks."""
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    if v_whole and bits > 2:
+        pytest.skip("wide codes: token-wise values only on the tuned kernels")
+    cases = []
+    for w in (synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=2304, n_text=200),
+              synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=1280, n_text=70)):
+        lay = H.layout_of(w, bits, w.n_vis, w.n_vis if v_whole else 128, 0, 0 if v_whole else 1)
+        cases.append(Case(w, lay))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        for c in cases:
+            c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+            c.check(cq.CQ_CALIB_NONE, n_text=0)
+        monkeypatch.setenv("CQ_DECODE_CHUNKS", "3")
+        for c in cases:
+            c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+            c.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
+    finally:
+        cq.cq_set_kernel_path(prev)
+
+
 @pytest.mark.parametrize("chunks", [2, 3])
 def test_tuned_channelwise_values_on_split_rows(kernel_path, chunks, monkeypatch):
     if kernel_path != "auto":

@@ -139,6 +139,32 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path, bits, group):
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.parametrize("bits", [1, 2, 4, 8])
+@pytest.mark.parametrize("n_vis", [256, 640, 2304])
+def test_tuned_whole_sequence_statistics(kernel_path, bits, n_vis):
+    """Sec. 3.1 as printed (one pair per channel over all tokens, keys and values) on the tuned
+    kernels: extrema pass + tile pass, with exact ties, a constant channel, signed zeros and rows
+    whose extreme elements sit in the first and in the last tile."""
+    if kernel_path != "auto":
+        pytest.skip("runs once")
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        w = synth.WORKLOADS[4].replace(batch=2, n_kv_heads=2, n_q_heads=2, n_vis=n_vis)
+        x = synth.make_inputs(w, "cpu", parts=("k", "v"))
+        x["k"][0, 0, :, 2] = torch.tensor([0.0, 1.0, 0.5, 0.25] * (n_vis // 4))
+        x["k"][0, 0, :, 3] = torch.tensor([0.0, 3.0, 0.5, 1.5, 2.5, 1.0, 2.0, 3.0] * (n_vis // 8))
+        x["k"][0, 1, :, 9] = 0.75
+        x["k"][1, 0, :, 11] = torch.tensor([-0.0, 0.0] * (n_vis // 2))
+        x["k"][1, 1, 0, 5] = 900.0            # the row's maximum in its first tile
+        x["k"][1, 1, n_vis - 1, 6] = -900.0   # the row's minimum in its last token
+        x["v"][1, 0, :, 7] = torch.tensor([0.0, 3.0, 0.5, 1.5, 2.5, 1.0, 2.0, 3.0] * (n_vis // 8))
+        x["v"][1, 1, :, 9] = -2.5
+        x["v"][0, 0, n_vis // 2, 64] = 60000.0
+        _run(w, H.layout_of(w, bits, n_vis, n_vis, 0, 0), x, what="whole sequence b=%d" % bits)
+    finally:
+        cq.cq_set_kernel_path(prev)
+
+
 @pytest.mark.parametrize("bits,group", [(1, 128), (2, 32), (4, 64), (8, 128)])
 def test_full_size_quantizer_config_on_sampled_rows(kernel_path, bits, group):
     """configs[3] at full size (batch 128, 8 KV heads, 16384 tokens), drawn on the GPU as
