@@ -17,6 +17,8 @@ What each function follows
   calibrate                    Sec. 3.2, the linear map g
   decode_attn                  Sec. 2.1 softmax(.)V with Sec. 3.2's g on the visual
                                logits and the 16-bit text tail of Sec. 3 / Sec. 3.3
+  softmax_mse / tau_grid_mse   Sec. 3.2, the grid search over tau1, tau2, scored by the
+                               error measure of the section's second figure (reading R7)
 
 Readings taken where the paper is silent (every one is repeated in the design notes)
   R1  Rounding operator of the quantize equation: exact real arithmetic, ties to even.
@@ -34,6 +36,11 @@ Readings taken where the paper is silent (every one is repeated in the design no
       one query row (after the 1/sqrt(d) scaling); text logits are neither included
       nor transformed; the softmax is joint.  delta == gamma gives slope 1.
   R6  Query head hq reads KV head hq // (Hq / Hkv).
+  R7  The paper searches tau1, tau2 on a grid but does not print the criterion; the
+      section's figure scores calibration by the mean squared error of the attention
+      weights against those of the exact keys, so the search takes that: per query row
+      the mean over all attended tokens (visual and text, joint softmax on both sides)
+      of the squared difference of the weights, averaged over the rows.
 
 parity unpinned: the values of tau1, tau2 (the paper searches {0,1,2,3}^2 but does
 not print the winners), the per-token value axis, the group sizes and the fp32
@@ -222,6 +229,52 @@ def decode_attn(q, kq: dict, vq: dict, k_text=None, v_text=None, n_text: int = 0
             if return_parts:
                 parts.append((s_vis, s_txt, w))
     return (out, parts) if return_parts else out
+
+
+# ----------------------------------------------------------------------------- tau search
+def _softmax(s):
+    s = np.asarray(s, np.float64)
+    e = np.exp(s - s.max())
+    return e / e.sum()
+
+
+def softmax_mse(s_exact, s_quant, s_text, tau1: float, tau2: float) -> float:
+    """Mean squared difference between the attention weights of one query row with the
+    calibrated quantized visual logits, softmax([g(s_quant), s_text]), and those with the
+    exact visual logits, softmax([s_exact, s_text])  (Sec. 3.2; gamma, delta as in R5)."""
+    s_text = np.asarray(s_text, np.float64)
+    p_ref = _softmax(np.concatenate([np.asarray(s_exact, np.float64), s_text]))
+    p_cal = _softmax(np.concatenate([calibrate(s_quant, tau1, tau2, CALIB_DYNAMIC), s_text]))
+    return float(np.mean((p_cal - p_ref) ** 2))
+
+
+def tau_grid_mse(q, k_exact, kq: dict, k_text=None, n_text: int = 0, tau1_grid=(0, 1, 2, 3),
+                 tau2_grid=(0, 1, 2, 3), softmax_scale: float = 0.0) -> np.ndarray:
+    """The grid search of Sec. 3.2: for every (tau1, tau2) of the grid, softmax_mse averaged
+    over all (batch, query head) rows.  q [B, Hq, d]; k_exact [B, Hkv, n_vis, d] the 16-bit
+    keys that kq quantizes; k_text [B, Hkv, >= n_text, d].  Returns [len(tau1_grid),
+    len(tau2_grid)] in fp64; the search result is its argmin."""
+    q = np.asarray(q, np.float64)
+    B, Hq, d = q.shape
+    k_deq = dequantize(kq["codes"], kq["scale"], kq["min"], kq["axis"], kq["group"])
+    Hkv = k_deq.shape[1]
+    g = Hq // Hkv
+    if softmax_scale == 0.0:
+        softmax_scale = 1.0 / np.sqrt(float(d))
+    out = np.zeros((len(tau1_grid), len(tau2_grid)), dtype=np.float64)
+    for b in range(B):
+        for hq in range(Hq):
+            h = hq // g
+            s_exact = logits_dequant(q[b, hq], np.asarray(k_exact[b, h], np.float64), softmax_scale)
+            s_quant = logits_dequant(q[b, hq], k_deq[b, h], softmax_scale)
+            if n_text > 0:
+                s_text = (np.asarray(k_text[b, h, :n_text], np.float64) @ q[b, hq]) * softmax_scale
+            else:
+                s_text = np.zeros((0,))
+            for i, t1 in enumerate(tau1_grid):
+                for j, t2 in enumerate(tau2_grid):
+                    out[i, j] += softmax_mse(s_exact, s_quant, s_text, float(t1), float(t2))
+    return out / float(B * Hq)
 
 
 def rel_l2(a, b) -> float:
