@@ -56,6 +56,8 @@ def main() -> int:
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="how the timed steps are launched: replay of one HIP graph holding all "
                          "of them (a serving loop's way), or one call per step from Python")
+    ap.add_argument("--tau-search", action="store_true",
+                    help="also run and time the grid search of the calibration parameters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="override the batch (debugging only)")
@@ -288,6 +290,29 @@ def main() -> int:
                          "cache_bytes_ratio": bytes16 / bytes_call}
         del sets16, ws16
 
+    # ---- optional: the grid search of tau1, tau2 (Sec. 3.2) on the first input set
+    tau_search = None
+    if args.tau_search:
+        xs = synth.make_inputs(w, dev, seed=w.seed)
+        k_s, _ = cq.cq_quantize_kv(lay, xs["k"], xs["v"])
+        del xs["v"]
+        grid = (0.0, 1.0, 2.0, 3.0)
+        ws_t = torch.empty(cq.cq_tau_search_workspace_bytes(lay, w.n_text, 4, 4), dtype=torch.uint8,
+                           device=dev)
+        kt_s = xs["k_text"] if w.n_text > 0 else None
+        run = lambda: cq.cq_tau_search(lay, xs["q"], xs["k"], k_s, kt_s, w.n_text, grid, grid, 0.0, ws_t)
+        mse = run()
+        torch.cuda.synchronize()
+        t_med, t_min = timed(run, 3)
+        mse = mse.cpu().numpy()
+        i1, i2 = divmod(int(mse.argmin()), 4)
+        tau_search = {"ms": t_med, "grid": list(grid), "mse": [[float(v) for v in r] for r in mse],
+                      "best_tau1_tau2": [grid[i1], grid[i2]], "mse_without_calibration": float(mse[0][0]),
+                      "workspace_bytes": ws_t.numel(),
+                      "note": "mean squared error of the attention weights against those of the exact "
+                              "keys, synthetic keys; shape-agnostic logits kernels + fp64 weights"}
+        del xs, k_s, ws_t
+
     # one plain copy of known size: the launch that byte counters (FETCH_SIZE / WRITE_SIZE) are
     # scaled with when this command runs under rocprofv3 --pmc
     cq.cq_bench_stream_copy(probe[nb:], probe, nb)
@@ -358,6 +383,7 @@ def main() -> int:
                      "bytes_per_visual_token_per_kv_head": per_vis,
                      "bytes_per_text_token_per_kv_head": per_text},
         "fp16_baseline": fp16_baseline,
+        "tau_search": tau_search,
         "quantizer": {"ms": q_ms, "bytes_read_plus_written": q_bytes, "reads_of_k_plus_v": q_reads,
                       "GB/s": q_bytes / (q_ms * 1e-3) / 1e9,
                       "frac_of_hbm_peak": q_bytes / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -152,6 +152,36 @@ int cq_append_text_kv(const cq_layout_t *layout, void *k_text_f16, void *v_text_
                       int32_t n_text, int32_t n_text_cap, const void *k_new_f16,
                       const void *v_new_f16, void *stream);
 
+/* Grid search of the calibration parameters (Sec. 3.2: tau1, tau2 are searched on a grid once and
+ * then fixed).  For every pair (tau1[i], tau2[j]) computes the mean squared difference between
+ * the attention weights softmax([g(q K_deq^T s), q K_text^T s]) over the quantized keys `k`, with
+ * gamma, delta the extrema of each row's visual logits as in CQ_CALIB_DYNAMIC, and the weights
+ * softmax([q K^T s, q K_text^T s]) over the exact keys; the mean runs over the n_vis + n_text
+ * attended tokens of a query row and then over the B * Hq rows (the error measure of the section's
+ * second figure).  The caller takes the argmin.
+ *   q_f16        in : fp16 [B, Hq, d] (device)
+ *   k_exact_f16  in : fp16 [B, Hkv, n_vis, d] (device), the keys that `k` quantizes
+ *   k            in : quantized keys of `layout` (device)
+ *   k_text_f16   in : fp16 [B, Hkv, n_text_cap, d] (device); may be NULL when n_text == 0
+ *   tau1, tau2   in : HOST arrays of n_tau1 and n_tau2 finite values, read before the call
+ *                     returns; 1 <= n_tau1 * n_tau2 <= 64
+ *   softmax_scale   : 0 means 1/sqrt(d)
+ *   mse_out      out: double [n_tau1][n_tau2] (device, 8-byte aligned)
+ *   workspace       : device scratch of at least cq_tau_search_workspace_bytes(), 256-byte
+ *                     aligned (the logits of both key sets: 4 * B * Hq * (2 n_vis + n_text) bytes
+ *                     and a little more)
+ * Works for every layout of the keys; the values play no part.  A calibration-time utility: its
+ * kernels are plain (fp64 weights).  Errors: CQ_ERR_NULL, CQ_ERR_ALIGN, CQ_ERR_SHAPE (n_vis == 0,
+ * grid size, non-finite tau), CQ_ERR_WORKSPACE, CQ_ERR_HIP.  Asynchronous on `stream`; allocates
+ * nothing.  cq_tau_search_workspace_bytes returns 0 for an invalid layout or grid. */
+size_t cq_tau_search_workspace_bytes(const cq_layout_t *layout, int32_t n_text, int32_t n_tau1,
+                                     int32_t n_tau2);
+int cq_tau_search(const cq_layout_t *layout, const void *q_f16, const void *k_exact_f16,
+                  const cq_qtensor_t *k, const void *k_text_f16, int32_t n_text,
+                  int32_t n_text_cap, const float *tau1, int32_t n_tau1, const float *tau2,
+                  int32_t n_tau2, float softmax_scale, double *mse_out, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
 /* Kernel selection, for tests and comparisons.  AUTO picks the tuned kernels when the
  * shape allows and the generic ones otherwise; GENERIC forces the shape-agnostic
  * kernels; TUNED returns CQ_ERR_UNSUPPORTED instead of falling back.  Process-wide.

@@ -65,6 +65,12 @@ def lib() -> ctypes.CDLL:
                                      P(CqCalib), ctypes.c_float, V, V, ctypes.c_size_t, V]
         L.cq_append_text_kv.restype = ctypes.c_int
         L.cq_append_text_kv.argtypes = [P(CqLayout), V, V, I, I, V, V, V]
+        L.cq_tau_search_workspace_bytes.restype = ctypes.c_size_t
+        L.cq_tau_search_workspace_bytes.argtypes = [P(CqLayout), I, I, I]
+        L.cq_tau_search.restype = ctypes.c_int
+        L.cq_tau_search.argtypes = [P(CqLayout), V, V, P(CqQTensor), V, I, I,
+                                    P(ctypes.c_float), I, P(ctypes.c_float), I, ctypes.c_float, V, V,
+                                    ctypes.c_size_t, V]
         L.cq_set_kernel_path.restype = ctypes.c_int
         L.cq_set_kernel_path.argtypes = [ctypes.c_int]
         L.cq_bench_stream_read.restype = ctypes.c_int
@@ -196,6 +202,36 @@ def cq_append_text_kv(layout: CqLayout, k_text: torch.Tensor, v_text: torch.Tens
     _check(lib().cq_append_text_kv(ctypes.byref(layout), _ptr(k_text), _ptr(v_text), int(n_text),
                                    int(k_text.shape[2]), _ptr(k_new), _ptr(v_new), _stream(k_text)))
     return int(n_text) + 1
+
+
+def cq_tau_search_workspace_bytes(layout: CqLayout, n_text: int, n_tau1: int, n_tau2: int) -> int:
+    return int(lib().cq_tau_search_workspace_bytes(ctypes.byref(layout), int(n_text), int(n_tau1),
+                                                   int(n_tau2)))
+
+
+def cq_tau_search(layout: CqLayout, q: torch.Tensor, k_exact: torch.Tensor, k: QTensor,
+                  k_text: Optional[torch.Tensor], n_text: int, tau1=(0.0, 1.0, 2.0, 3.0),
+                  tau2=(0.0, 1.0, 2.0, 3.0), softmax_scale: float = 0.0,
+                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Mean squared error of the attention weights for every (tau1, tau2) of the grid, as a
+    float64 tensor [len(tau1), len(tau2)] on the device; its argmin is the search result."""
+    assert q.dtype == torch.float16 and k_exact.dtype == torch.float16
+    assert q.is_contiguous() and k_exact.is_contiguous()
+    if k_text is not None:
+        assert k_text.dtype == torch.float16 and k_text.is_contiguous()
+    t1 = (ctypes.c_float * len(tau1))(*[float(t) for t in tau1])
+    t2 = (ctypes.c_float * len(tau2))(*[float(t) for t in tau2])
+    need = cq_tau_search_workspace_bytes(layout, n_text, len(tau1), len(tau2))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    out = torch.empty((len(tau1), len(tau2)), dtype=torch.float64, device=q.device)
+    cap = 0 if k_text is None else int(k_text.shape[2])
+    ks = k.c_struct()
+    _check(lib().cq_tau_search(ctypes.byref(layout), _ptr(q), _ptr(k_exact), ctypes.byref(ks),
+                               _ptr(k_text), int(n_text), cap, t1, len(tau1), t2, len(tau2),
+                               float(softmax_scale), _ptr(out), _ptr(workspace),
+                               workspace.numel(), _stream(q)))
+    return out
 
 
 def cq_bench_stream_read(buf: torch.Tensor, nbytes: int) -> None:

@@ -68,6 +68,19 @@ int check_qtensor(const char* which, const cq_qtensor_t* t) {
   return CQ_OK;
 }
 
+cq::DecodeShape make_shape(const cq_layout_t* L, int n_text, int n_text_cap) {
+  cq::DecodeShape s;
+  s.B = L->batch; s.Hq = L->n_q_heads; s.Hkv = L->n_kv_heads; s.g = s.Hq / s.Hkv;
+  s.d = L->head_dim; s.n_vis = L->n_vis; s.n_text = n_text; s.n_text_cap = n_text_cap;
+  s.bits = L->bits; s.k_axis = L->k_axis; s.v_axis = L->v_axis;
+  s.k_group = L->k_group; s.v_group = L->v_group;
+  s.n_vis_chunks = cq::ceil_div(s.n_vis, cq::kVisChunk);
+  s.n_text_chunks = cq::ceil_div(s.n_text, cq::kTextChunk);
+  s.n_chunks = s.n_vis_chunks + s.n_text_chunks;
+  s.words_per_token = s.d * s.bits / 32;
+  return s;
+}
+
 int hip_fail(hipError_t e, const char* what) {
   return fail(CQ_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
@@ -217,15 +230,7 @@ int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* 
     return fail(CQ_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes,
                 wl.total_bytes);
 
-  cq::DecodeShape s;
-  s.B = L->batch; s.Hq = L->n_q_heads; s.Hkv = L->n_kv_heads; s.g = s.Hq / s.Hkv;
-  s.d = L->head_dim; s.n_vis = L->n_vis; s.n_text = n_text; s.n_text_cap = n_text_cap;
-  s.bits = L->bits; s.k_axis = L->k_axis; s.v_axis = L->v_axis;
-  s.k_group = L->k_group; s.v_group = L->v_group;
-  s.n_vis_chunks = cq::ceil_div(s.n_vis, cq::kVisChunk);
-  s.n_text_chunks = cq::ceil_div(s.n_text, cq::kTextChunk);
-  s.n_chunks = s.n_vis_chunks + s.n_text_chunks;
-  s.words_per_token = s.d * s.bits / 32;
+  const cq::DecodeShape s = make_shape(L, n_text, n_text_cap);
 
   static const cq_qtensor_t kNone = {nullptr, nullptr, nullptr};
   const cq_qtensor_t& kq = k ? *k : kNone;
@@ -243,6 +248,63 @@ int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* 
     e = cq::launch_decode_generic(s, q_f16, kq, vq, k_text_f16, v_text_f16, c, softmax_scale,
                                   out_f16, static_cast<float*>(workspace), wl, st);
   if (e != hipSuccess) return hip_fail(e, "decode attention");
+  return CQ_OK;
+}
+
+size_t cq_tau_search_workspace_bytes(const cq_layout_t* L, int32_t n_text, int32_t n_tau1,
+                                     int32_t n_tau2) {
+  if (check_layout(L, true) != CQ_OK || n_text < 0 || n_tau1 < 1 || n_tau2 < 1 ||
+      (long long)n_tau1 * n_tau2 > cq::kMaxTauPairs)
+    return 0;
+  return cq::tau_workspace_layout(L->batch, L->n_q_heads, L->n_vis, n_text, n_tau1 * n_tau2)
+      .total_bytes;
+}
+
+int cq_tau_search(const cq_layout_t* L, const void* q_f16, const void* k_exact_f16,
+                  const cq_qtensor_t* k, const void* k_text_f16, int32_t n_text, int32_t n_text_cap,
+                  const float* tau1, int32_t n_tau1, const float* tau2, int32_t n_tau2,
+                  float softmax_scale, double* mse_out, void* workspace, size_t workspace_bytes,
+                  void* stream) {
+  int rc = check_layout(L, true);
+  if (rc != CQ_OK) return rc;
+  if (L->n_vis < 1) return fail(CQ_ERR_SHAPE, "no quantized tokens to calibrate: n_vis == 0");
+  if (!q_f16 || !k_exact_f16 || !mse_out || !tau1 || !tau2)
+    return fail(CQ_ERR_NULL, "q_f16, k_exact_f16, tau1, tau2 or mse_out is NULL");
+  if (!aligned16(q_f16) || !aligned16(k_exact_f16))
+    return fail(CQ_ERR_ALIGN, "q_f16 and k_exact_f16 must be 16-byte aligned");
+  if ((reinterpret_cast<uintptr_t>(mse_out) & 7u) != 0)
+    return fail(CQ_ERR_ALIGN, "mse_out must be 8-byte aligned");
+  if ((rc = check_qtensor("k", k)) != CQ_OK) return rc;
+  if (n_text < 0 || n_text_cap < n_text)
+    return fail(CQ_ERR_SHAPE, "need 0 <= n_text (%d) <= n_text_cap (%d)", n_text, n_text_cap);
+  if (n_text > 0) {
+    if (!k_text_f16) return fail(CQ_ERR_NULL, "n_text=%d but k_text_f16 is NULL", n_text);
+    if (!aligned16(k_text_f16)) return fail(CQ_ERR_ALIGN, "k_text_f16 must be 16-byte aligned");
+  }
+  if (n_tau1 < 1 || n_tau2 < 1 || (long long)n_tau1 * n_tau2 > cq::kMaxTauPairs)
+    return fail(CQ_ERR_SHAPE, "the grid needs 1 <= n_tau1 * n_tau2 <= %d pairs (got %d x %d)",
+                cq::kMaxTauPairs, n_tau1, n_tau2);
+  for (int i = 0; i < n_tau1; ++i)
+    if (!std::isfinite(tau1[i])) return fail(CQ_ERR_SHAPE, "tau1[%d] is not finite", i);
+  for (int i = 0; i < n_tau2; ++i)
+    if (!std::isfinite(tau2[i])) return fail(CQ_ERR_SHAPE, "tau2[%d] is not finite", i);
+  if (!std::isfinite(softmax_scale) || softmax_scale < 0.f)
+    return fail(CQ_ERR_SHAPE, "softmax_scale must be finite and >= 0");
+  if (softmax_scale == 0.f) softmax_scale = 1.0f / std::sqrt((float)L->head_dim);
+  const cq::TauWorkspace wl =
+      cq::tau_workspace_layout(L->batch, L->n_q_heads, L->n_vis, n_text, n_tau1 * n_tau2);
+  if (!workspace) return fail(CQ_ERR_WORKSPACE, "workspace is NULL");
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(CQ_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (workspace_bytes < wl.total_bytes)
+    return fail(CQ_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes,
+                wl.total_bytes);
+  const cq::DecodeShape s = make_shape(L, n_text, n_text_cap);
+  const hipError_t e = cq::launch_tau_search(s, q_f16, k_exact_f16, *k, k_text_f16, tau1, n_tau1,
+                                             tau2, n_tau2, softmax_scale, mse_out,
+                                             static_cast<float*>(workspace), wl,
+                                             static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "tau search");
   return CQ_OK;
 }
 

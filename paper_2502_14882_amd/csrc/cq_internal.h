@@ -62,6 +62,44 @@ hipError_t launch_decode_generic(const DecodeShape& s, const void* q, const cq_q
                                  const Calib& calib, float softmax_scale, void* out,
                                  float* workspace, const Workspace& wl, hipStream_t stream);
 
+// First stage of the shape-agnostic decode on its own: raw logits [B*Hq][n_vis + n_text] and the
+// extrema [B*Hq][n_chunks][2] of every chunk of tokens.
+hipError_t launch_scores_generic(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
+                                 const void* k_text, float softmax_scale, float* logits,
+                                 float* minmax, hipStream_t stream);
+
+// Grid search of the calibration parameters (Sec. 3.2): workspace layout in floats, and launcher.
+constexpr int kMaxTauPairs = 64;
+struct TauWorkspace {
+  size_t logits_q;   // [B*Hq][n_vis + n_text]  logits on the dequantized keys and the text keys
+  size_t logits_x;   // [B*Hq][n_vis]           logits on the exact 16-bit keys
+  size_t minmax_q;   // [B*Hq][chunks of n_vis + n_text][2]
+  size_t minmax_x;   // [B*Hq][chunks of n_vis][2]
+  size_t row_mse;    // [B*Hq][n_pairs] doubles
+  size_t total_bytes;
+};
+inline TauWorkspace tau_workspace_layout(int B, int Hq, int n_vis, int n_text, int n_pairs) {
+  TauWorkspace w;
+  const int nvc = ceil_div(n_vis, kVisChunk), ntc = ceil_div(n_text, kTextChunk);
+  // the exact keys go through the text-tail path of the logits kernel: chunks of kTextChunk
+  const int nxc = ceil_div(n_vis, kTextChunk);
+  const size_t rows = (size_t)B * (size_t)Hq;
+  auto align64 = [](size_t x) { return (x + 63) / 64 * 64; };
+  w.logits_q = 0;
+  w.logits_x = align64(w.logits_q + rows * ((size_t)n_vis + (size_t)n_text));
+  w.minmax_q = align64(w.logits_x + rows * (size_t)n_vis);
+  w.minmax_x = align64(w.minmax_q + rows * (size_t)(nvc + ntc) * 2);
+  w.row_mse = align64(w.minmax_x + rows * (size_t)nxc * 2);
+  const size_t end = align64(w.row_mse + rows * (size_t)n_pairs * 2);
+  w.total_bytes = (end * sizeof(float) + 255) / 256 * 256;
+  return w;
+}
+hipError_t launch_tau_search(const DecodeShape& s, const void* q, const void* k_exact,
+                             const cq_qtensor_t& k, const void* k_text, const float* tau1,
+                             int n_tau1, const float* tau2, int n_tau2, float softmax_scale,
+                             double* mse_out, float* workspace, const TauWorkspace& wl,
+                             hipStream_t stream);
+
 // Register-resident tile quantizer for head_dim 128, b in {1,2,4,8}, n_vis a multiple of 128,
 // groups of 32/64/128 or (channel axis) the whole sequence, which adds an extrema pass.
 bool quantize_tuned_supported(int n_vis, int d, int bits, int axis, int group);

@@ -222,6 +222,18 @@ hipError_t launch_combine(int n_rows, int n_chunks, int d, const float* partial,
   return hipGetLastError();
 }
 
+hipError_t launch_scores_generic(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
+                                 const void* k_text, float softmax_scale, float* logits,
+                                 float* minmax, hipStream_t stream) {
+  const size_t blocks = (size_t)s.B * s.Hkv * (size_t)s.n_chunks;
+  if (blocks > 0x7fffffffu) return hipErrorInvalidConfiguration;
+  QParams kp{k.codes, k.scale, k.min, s.k_axis, s.k_group};
+  scores_kernel<<<dim3((unsigned)blocks), dim3(kScoreThreads), 0, stream>>>(
+      s, static_cast<const __half*>(q), kp, static_cast<const __half*>(k_text), softmax_scale,
+      logits, minmax);
+  return hipGetLastError();
+}
+
 hipError_t launch_decode_generic(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
                                  const cq_qtensor_t& v, const void* k_text, const void* v_text,
                                  const Calib& calib, float softmax_scale, void* out,

@@ -102,6 +102,37 @@ def test_append_argument_errors():
     assert f(None, FAKE, FAKE, 0, 4, FAKE, FAKE, None) == cq.CQ_ERR_NULL
 
 
+def test_tau_search_argument_errors():
+    lay = cq.make_layout(2, 8, 2, 128, 256)
+    L = cq.lib()
+    need = cq.cq_tau_search_workspace_bytes(lay, 16, 4, 4)
+    assert need > 0 and need % 256 == 0
+    assert need >= 2 * 8 * (2 * 256 + 16) * 4        # the logits of both key sets
+    assert cq.cq_tau_search_workspace_bytes(lay, 16, 9, 8) == 0      # more than 64 pairs
+    assert cq.cq_tau_search_workspace_bytes(lay, 16, 0, 4) == 0
+    kq = cq.CqQTensor(FAKE, FAKE, FAKE)
+    grid = (ctypes.c_float * 4)(0.0, 1.0, 2.0, 3.0)
+    bad = (ctypes.c_float * 4)(0.0, float("nan"), 2.0, 3.0)
+
+    def call(lay=lay, q=FAKE, kx=FAKE, k=kq, kt=FAKE, n_text=16, cap=16, t1=grid, n1=4, t2=grid,
+             n2=4, scale=0.0, out=FAKE, ws=FAKE + 0x100, ws_bytes=need):
+        return L.cq_tau_search(ctypes.byref(lay), q, kx, ctypes.byref(k), kt, n_text, cap, t1, n1,
+                               t2, n2, scale, out, ws, ws_bytes, None)
+
+    assert call(kx=None) == cq.CQ_ERR_NULL
+    assert call(out=None) == cq.CQ_ERR_NULL
+    assert call(kt=None) == cq.CQ_ERR_NULL
+    assert call(q=FAKE + 2) == cq.CQ_ERR_ALIGN
+    assert call(out=FAKE + 4) == cq.CQ_ERR_ALIGN
+    assert call(n_text=17) == cq.CQ_ERR_SHAPE
+    assert call(n1=0) == cq.CQ_ERR_SHAPE
+    assert call(t2=bad) == cq.CQ_ERR_SHAPE
+    assert b"tau2[1]" in L.cq_last_error()
+    assert call(ws=None) == cq.CQ_ERR_WORKSPACE
+    assert call(ws_bytes=need - 256) == cq.CQ_ERR_WORKSPACE
+    assert call(lay=cq.make_layout(2, 8, 2, 128, 0)) == cq.CQ_ERR_SHAPE    # nothing quantized
+
+
 def test_workspace_size_rule():
     lay = cq.make_layout(2, 8, 2, 128, 1024)
     n = cq.cq_decode_workspace_bytes(lay, 32)
