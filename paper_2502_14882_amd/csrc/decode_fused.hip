@@ -107,6 +107,18 @@ struct FusedArgs {
 #define CQ_CLKW(k) do { } while (0)
 #endif
 
+// Load of cache data that the workgroup reads exactly once.  NT marks it non-temporal (measured on
+// a plain streaming read of the same bytes: 6.4-6.6 TB/s against 5.8 TB/s with ordinary loads).
+// That only pays where one instruction covers whole cache lines: a line that several instructions
+// touch in turn (the strided code words of 4- and 8-bit tokens) may be dropped in between and
+// fetched again, so those loads stay ordinary, and so do all loads of a workgroup whose twin on
+// the same XCD is meant to find the lines in L2 (two head blocks per KV head).
+template <bool NT, typename T>
+__device__ inline T stream_load(const T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+
 __device__ inline v2i lds_read_tr8(const uint8_t* p) {
   return __builtin_amdgcn_ds_read_tr8_b64_v2i32(
       (__attribute__((address_space(3))) v2i*)(p));
@@ -247,9 +259,12 @@ __device__ inline int code_in_word(int y, int v) {
 // token-wise.
 // KW = key statistics over the whole sequence: one parameter group per row, so the query operand,
 // its shift and the additive term are formed once per wave instead of once per 128 tokens.
-template <int TILES, int BITS, bool VCH, bool KW = false>
+template <int TILES, int BITS, bool VCH, bool KW = false, bool NT = true>
 __global__ void __launch_bounds__(kThreads)
 fused_row_kernel(const FusedArgs a) {
+  // code words, see stream_load: a key instruction covers whole lines up to b = 4, a value
+  // instruction up to b = 2 (wider value codes are read token by token in 16-byte pieces)
+  constexpr bool kNtKeys = NT && BITS <= 4, kNtCodes = NT && BITS <= 2;
   static_assert(!KW || TILES == 8, "whole-sequence keys are processed 128 tokens at a time");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // workgroup = (row = b * Hkv + kvh, block of 4 query heads, chunk of the row's tokens)
@@ -376,14 +391,29 @@ fused_row_kernel(const FusedArgs a) {
       uint32_t m01[kRK];          // their minima, two fp16 in one word
       auto load_group = [&](int slot, int t) {
         const int tc = min(t, n_groups - 1);      // clamped, never a branch around a load
+        // a lane's b words of a tile are adjacent: one load of 4b bytes (two of 16 for b = 8), so
+        // that an instruction covers whole cache lines
 #pragma unroll
-        for (int i = 0; i < TILES; ++i)
+        for (int i = 0; i < TILES; ++i) {
+          const uint32_t* p = kc_lane + ((size_t)tc * TILES + i) * (64 * BITS);
+          if constexpr (BITS == 1) {
+            w[slot][i][0] = stream_load<kNtKeys>(p);
+          } else if constexpr (BITS == 2) {
+            const v2i t2 = stream_load<kNtKeys>(reinterpret_cast<const v2i*>(p));
+            w[slot][i][0] = (uint32_t)t2[0];
+            w[slot][i][1] = (uint32_t)t2[1];
+          } else {
 #pragma unroll
-          for (int e = 0; e < BITS; ++e)
-            w[slot][i][e] = kc_lane[((size_t)tc * TILES + i) * (64 * BITS) + e];
+            for (int q4 = 0; q4 < BITS / 4; ++q4) {
+              const v4i t4 = stream_load<kNtKeys>(reinterpret_cast<const v4i*>(p) + q4);
+#pragma unroll
+              for (int u = 0; u < 4; ++u) w[slot][i][4 * q4 + u] = (uint32_t)t4[u];
+            }
+          }
+        }
         if constexpr (!KW) {
-          s01[slot] = *reinterpret_cast<const v2f*>(ks_row + (size_t)tc * a.k_pstride + wc0);
-          m01[slot] = *reinterpret_cast<const uint32_t*>(km_row + (size_t)tc * a.k_pstride + wc0);
+          s01[slot] = stream_load<NT>(reinterpret_cast<const v2f*>(ks_row + (size_t)tc * a.k_pstride + wc0));
+          m01[slot] = stream_load<NT>(reinterpret_cast<const uint32_t*>(km_row + (size_t)tc * a.k_pstride + wc0));
         }
       };
       // query operand of the key group whose parameters sit in ring slot `slot`, staged at xb
@@ -528,8 +558,8 @@ fused_row_kernel(const FusedArgs a) {
         for (int u = 0; u < 2; ++u) {
           const int tok = min(t0 + 8 * u, ntx - 1);
           const v8h* src = reinterpret_cast<const v8h*>(kt_row + (size_t)tok * kD);
-          kt[slot][2 * u] = src[0];            // channels 32 hsel + 8kb .. of line 0 (channels 0..63)
-          kt[slot][2 * u + 1] = src[8];        // the same of line 1 (channels 64..127)
+          kt[slot][2 * u] = stream_load<NT>(src);          // channels 32 hsel + 8kb .. of line 0 (channels 0..63)
+          kt[slot][2 * u + 1] = stream_load<NT>(src + 8);  // the same of line 1 (channels 64..127)
         }
       };
 #pragma unroll
@@ -676,10 +706,12 @@ fused_row_kernel(const FusedArgs a) {
       };
       v4i cg[kRingV][BITS];
       auto load_tile = [&](int slot, int k) {
-        const int j = tile_start(k) + lane;
+        // a tile's code bytes are contiguous (64 tokens x 16b bytes): instruction e takes the e-th KB,
+        // whole cache lines; the same image goes to LDS
+        const int j = tile_start(k);
 #pragma unroll
         for (int e = 0; e < BITS; ++e)
-          cg[slot][e] = *reinterpret_cast<const v4i*>(vc_row + (size_t)j * (4 * BITS) + 4 * e);
+          cg[slot][e] = stream_load<kNtCodes>(reinterpret_cast<const v4i*>(vc_row + (size_t)j * (4 * BITS) + 256 * e + 4 * lane));
       };
       v4f gsc[2];
       v2i gmn[2];
@@ -706,7 +738,7 @@ fused_row_kernel(const FusedArgs a) {
         *reinterpret_cast<v4i*>(lbytes + (size_t)jt * 4 + x_wr) = xs;
 #pragma unroll
         for (int e = 0; e < BITS; ++e)
-          *reinterpret_cast<v4i*>(stage + (BITS == 1 ? buf * 1024 : 0) + lane * (16 * BITS) + 16 * e) =
+          *reinterpret_cast<v4i*>(stage + (BITS == 1 ? buf * 1024 : 0) + 1024 * e + 16 * lane) =
               cg[slot][e];
       };
       v4i acc_w = {0, 0, 0, 0};
@@ -801,9 +833,9 @@ fused_row_kernel(const FusedArgs a) {
         const int j = min(jt, last) + lane;
 #pragma unroll
         for (int e = 0; e < BITS; ++e)
-          cg[slot][e] = *reinterpret_cast<const v4i*>(vc_row + (size_t)j * (4 * BITS) + 4 * e);
-        vsr[slot] = vs_row[j];
-        vmr[slot] = vm_row[j];
+          cg[slot][e] = stream_load<kNtCodes>(reinterpret_cast<const v4i*>(vc_row + (size_t)j * (4 * BITS) + 4 * e));
+        vsr[slot] = stream_load<NT>(vs_row + j);
+        vmr[slot] = stream_load<NT>(vm_row + j);
       };
       auto tile_step = [&](int jt, int slot) {
         if (__builtin_amdgcn_ballot_w64(vsr[slot] >= fit_below) != 0) {
@@ -894,12 +926,13 @@ fused_row_kernel(const FusedArgs a) {
       float vsr[kRingV];
       uint16_t vmr[kRingV];       // raw fp16 bits: converting here would wait for the load at once
       auto load_tile = [&](int slot, int jt) {
-        const int j = min(jt, last) + lane;
+        const int j0 = min(jt, last), j = j0 + lane;
+        // the tile's code bytes are contiguous: instruction e takes the e-th KB, whole cache lines
 #pragma unroll
         for (int e = 0; e < BITS; ++e)
-          cg[slot][e] = *reinterpret_cast<const v4i*>(vc_row + (size_t)j * (4 * BITS) + 4 * e);
-        vsr[slot] = vs_row[j];
-        vmr[slot] = vm_row[j];
+          cg[slot][e] = stream_load<kNtCodes>(reinterpret_cast<const v4i*>(vc_row + (size_t)j0 * (4 * BITS) + 256 * e + 4 * lane));
+        vsr[slot] = stream_load<NT>(vs_row + j);
+        vmr[slot] = stream_load<NT>(vm_row + j);
       };
       auto prep_tile = [&](int slot, int jt, int buf) {
         if (__builtin_amdgcn_ballot_w64(vsr[slot] >= fit_below) != 0) {
@@ -927,7 +960,7 @@ fused_row_kernel(const FusedArgs a) {
         // accesses in order, so the previous tile's reads are served before these writes)
 #pragma unroll
         for (int e = 0; e < BITS; ++e)
-          *reinterpret_cast<v4i*>(stage + (BITS == 1 ? buf * 1024 : 0) + lane * (16 * BITS) + 16 * e) =
+          *reinterpret_cast<v4i*>(stage + (BITS == 1 ? buf * 1024 : 0) + 1024 * e + 16 * lane) =
               cg[slot][e];
       };
       const int j_first = wave * 64;
@@ -1015,7 +1048,7 @@ fused_row_kernel(const FusedArgs a) {
       v8h ring[kDepth];
       auto load_step = [&](int slot, int blk, int s) {
         const int tok = min(min(blk, n_blocks - 1) * 64 + 4 * s + kb, ntx - 1);
-        ring[slot] = *reinterpret_cast<const v8h*>(vt_row + (size_t)tok * kD);
+        ring[slot] = stream_load<NT>(reinterpret_cast<const v8h*>(vt_row + (size_t)tok * kD));
       };
 #pragma unroll
       for (int s = 0; s < kDepth; ++s) load_step(s, tw, s);
@@ -1362,9 +1395,14 @@ hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq
     case (128 * 4 + 8) * 2: kern = fused_row_kernel<8, 8, false>; slot = 17; break;
     default: return hipErrorInvalidValue;
   }
+  // two head blocks per KV head: the twin workgroups share their lines through L2 (ordinary loads)
+  if (plan.nhb > 1 && !k_whole && !vch && s.k_group == 128 && s.bits <= 2) {
+    if (s.bits == 1) { kern = fused_row_kernel<8, 1, false, false, false>; slot = 24; }
+    else { kern = fused_row_kernel<8, 2, false, false, false>; slot = 25; }
+  }
   // the kernel's dynamic LDS limit is raised once per (device, kernel) and only ever grows;
   // concurrent callers may both raise it, which is harmless
-  static std::atomic<size_t> configured[kMaxDevices][24];
+  static std::atomic<size_t> configured[kMaxDevices][26];
   int dev = 0;
   hipError_t de = hipGetDevice(&dev);
   if (de != hipSuccess) return de;
