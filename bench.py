@@ -42,8 +42,8 @@ def algorithmic_bytes(w, bits, k_group, v_group):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list")
     ap.add_argument("--bits", type=int, default=1)
     ap.add_argument("--group", type=int, default=128,
