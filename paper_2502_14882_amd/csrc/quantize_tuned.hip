@@ -14,8 +14,9 @@
 //   3. codes by comparing packed halves against the thresholds (sign of t - x), bits gathered with
 //      v_perm + v_dot4, words assembled across adjacent lanes, MSB first as in the packing appendix.
 //   b in {4, 8} (too many thresholds): step 2 stores min and (2^b-1)/(max-min) per group, step 3
-//   evaluates the quantize equation per element in fp64 with that reciprocal and settles the
-//   rounding exactly (see exact_code); a lane's 8 channels fill one word (b = 4) or two (b = 8).
+//   evaluates the quantize equation per element with that reciprocal - in fp32 where that already
+//   decides the code, in fp64 with the rounding settled exactly (see exact_code) where it does
+//   not; a lane's 8 channels fill one word (b = 4) or two (b = 8).
 // Channel-wise statistics over the whole sequence (group = n_vis: one pair per channel, Sec. 3.1
 // as printed) take a pass of their own: row_extrema_kernel leaves kSplits partial (min, max)
 // pairs per channel in the code words of the row's LAST tile (the caller's output buffer: no
@@ -111,13 +112,30 @@ __device__ inline uint32_t exact_code(_Float16 x, double alpha, double rinv) {
   return c;
 }
 
-// the 8 codes of one octet as packed words, first channel in the top bits (packing appendix)
+// the 8 codes of one octet as packed words, first channel in the top bits (packing appendix).
+// Fast path in fp32 with alpha32 = alpha and rinv32 = fl32(rinv): q32 = fl(fl(x - alpha) * rinv32)
+// carries three roundings, so it is within L * 3 * 2^-24 of the true quotient (L = 2^b - 1 bounds
+// the quotient).  Unless q32 lies within L * 2^-22 of a half-integer, rounding it to nearest gives
+// the exact code; an octet with any element inside that band (8-bit codes: ~0.1 % of the octets)
+// is redone by exact_code.
 template <int BITS>
 __device__ inline void octet_words(const v8h& x, const double (&alpha)[8], const double (&rinv)[8],
+                                   const float (&alpha32)[8], const float (&rinv32)[8],
                                    uint32_t& w0, uint32_t& w1) {
+  constexpr float kBand = (float)((1 << BITS) - 1) * 0x1p-22f;
   uint32_t c[8];
+  bool unsure = false;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) c[j] = exact_code(x[j], alpha[j], rinv[j]);
+  for (int j = 0; j < 8; ++j) {
+    const float q = ((float)x[j] - alpha32[j]) * rinv32[j];
+    const float r = rintf(q);
+    c[j] = (uint32_t)(int)r;
+    unsure |= 0.5f - fabsf(q - r) <= kBand;
+  }
+  if (unsure) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) c[j] = exact_code(x[j], alpha[j], rinv[j]);
+  }
   if constexpr (BITS == 4) {
     w0 = 0;
 #pragma unroll
@@ -323,16 +341,19 @@ quantize_tile_kernel(const QArgs a) {
     const int g = (32 * wave) / kG;
     if constexpr (kWide) {
       double al[8], ri[8];
+      float al32[8], ri32[8];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        al[j] = (double)(float)s_alpha[g * kD + c8 * 8 + j];
+        al32[j] = (float)s_alpha[g * kD + c8 * 8 + j];
+        al[j] = (double)al32[j];
         ri[j] = s_rinv[g * kD + c8 * 8 + j];
+        ri32[j] = (float)ri[j];
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int tok = 32 * wave + 4 * i + ts;
         uint32_t w0, w1;
-        octet_words<BITS>(x[i], al, ri, w0, w1);
+        octet_words<BITS>(x[i], al, ri, al32, ri32, w0, w1);
         if constexpr (BITS == 4) {
           s_codes[tok * kWords + c8] = w0;
         } else {
@@ -412,10 +433,14 @@ quantize_tile_kernel(const QArgs a) {
     for (int i = 0; i < 8; ++i) {
       const int tok = 32 * wave + 4 * i + ts;
       if constexpr (kWide) {
-        const double a1 = (double)(float)s_alpha[tok * 4 + g], r1 = s_rinv[tok * 4 + g];
+        const float a32 = (float)s_alpha[tok * 4 + g];
+        const double a1 = (double)a32, r1 = s_rinv[tok * 4 + g];
+        const float r32 = (float)r1;
         const double al[8] = {a1, a1, a1, a1, a1, a1, a1, a1}, ri[8] = {r1, r1, r1, r1, r1, r1, r1, r1};
+        const float al32[8] = {a32, a32, a32, a32, a32, a32, a32, a32};
+        const float ri32[8] = {r32, r32, r32, r32, r32, r32, r32, r32};
         uint32_t w0, w1;
-        octet_words<BITS>(x[i], al, ri, w0, w1);
+        octet_words<BITS>(x[i], al, ri, al32, ri32, w0, w1);
         if constexpr (BITS == 4) {
           s_codes[tok * kWords + c8] = w0;
         } else {
