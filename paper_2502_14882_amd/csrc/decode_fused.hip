@@ -48,8 +48,10 @@ constexpr int kHeads = 4;           // query heads per matrix pass (4 digits x 4
 constexpr int kStageBytes = 2048;   // LDS staging per visual wave
 constexpr int kRedPerHead = 6;
 // loads in flight per wave, in units of one key group / value tile / text tile / 4 text tokens.
-// Deeper is not better on this chip: with much more than ~32 KB in flight per CU the achieved
-// bandwidth drops (also seen on a plain streaming read).
+// Deeper is not better on this chip: with much more in flight per CU the achieved bandwidth drops
+// (also seen on a plain streaming read).  Measured: on long whole rows (64 key groups) 3 key
+// groups in flight are 1-2 % faster than 2 and 4 are 8 % slower, on short or split rows 3 are 3-5 %
+// slower (the kernel's RK parameter); the other rings make no difference.
 #ifndef CQ_RING_K
 #define CQ_RING_K 2
 #endif
@@ -259,7 +261,7 @@ __device__ inline int code_in_word(int y, int v) {
 // token-wise.
 // KW = key statistics over the whole sequence: one parameter group per row, so the query operand,
 // its shift and the additive term are formed once per wave instead of once per 128 tokens.
-template <int TILES, int BITS, bool VCH, bool KW = false, bool NT = true>
+template <int TILES, int BITS, bool VCH, bool KW = false, bool NT = true, int RK = kRingK>
 __global__ void __launch_bounds__(kThreads)
 fused_row_kernel(const FusedArgs a) {
   // code words, see stream_load: a key instruction covers whole lines up to b = 4, a value
@@ -385,7 +387,7 @@ fused_row_kernel(const FusedArgs a) {
 
       // wide codes are 4 or 8 words per lane and tile: one group in the ring is all that fits
       // (the depth of this ring was measured to make no difference)
-      constexpr int kRK = BITS > 2 ? 1 : kRingK;
+      constexpr int kRK = BITS > 2 ? 1 : RK;
       uint32_t w[kRK][TILES][BITS];
       v2f s01[kRK];               // scales of channels wc0, wc1
       uint32_t m01[kRK];          // their minima, two fp16 in one word
@@ -1395,6 +1397,12 @@ hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq
     case (128 * 4 + 8) * 2: kern = fused_row_kernel<8, 8, false>; slot = 17; break;
     default: return hipErrorInvalidValue;
   }
+  // long whole rows: three key groups in flight per wave
+  if (plan.n_chunks == 1 && plan.nhb == 1 && !k_whole && !vch && s.k_group == 128 && s.bits <= 2 &&
+      s.n_vis >= 48 * 128) {
+    if (s.bits == 1) { kern = fused_row_kernel<8, 1, false, false, true, 3>; slot = 26; }
+    else { kern = fused_row_kernel<8, 2, false, false, true, 3>; slot = 27; }
+  }
   // two head blocks per KV head: the twin workgroups share their lines through L2 (ordinary loads)
   if (plan.nhb > 1 && !k_whole && !vch && s.k_group == 128 && s.bits <= 2) {
     if (s.bits == 1) { kern = fused_row_kernel<8, 1, false, false, false>; slot = 24; }
@@ -1402,7 +1410,7 @@ hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq
   }
   // the kernel's dynamic LDS limit is raised once per (device, kernel) and only ever grows;
   // concurrent callers may both raise it, which is harmless
-  static std::atomic<size_t> configured[kMaxDevices][26];
+  static std::atomic<size_t> configured[kMaxDevices][28];
   int dev = 0;
   hipError_t de = hipGetDevice(&dev);
   if (de != hipSuccess) return de;
