@@ -779,7 +779,11 @@ fused_row_kernel(const FusedArgs a) {
           acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B, acc[p], 0, 0, 0);
         }
         acc_w = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, ones, acc_w, 0, 0, 0);
-        if ((k & (tpg - 1)) == tpg - 1) {       // last tile of a value group: fold it into fp32
+        // last tile of a value group: fold it into fp32.  With whole-sequence statistics every
+        // group has the row's parameters, so the wave folds once, after its last tile (an int32
+        // accumulator takes 2^20 per tile at most: 2047 tiles, a workgroup's LDS holds ~140)
+        const bool fold = a.v_pstride == 0 ? k == n_my - 1 : (k & (tpg - 1)) == tpg - 1;
+        if (fold) {
           const float wsum = digits_to_float(acc_w);
           acc_w = (v4i){0, 0, 0, 0};
 #pragma unroll
