@@ -59,7 +59,9 @@ __device__ inline uint16_t threshold_bits(double alpha, double D, int k, int L) 
     const double lhs = twoL * (h_to_double(u) - alpha);
     return strict ? lhs > rhs : lhs >= rhs;
   };
-  uint16_t t = __half_as_ushort(__float2half_rn((float)(alpha + rhs / twoL)));
+  // candidate: the real-valued boundary, good to an fp16 step (the reciprocal of 2L is a compile-time
+  // constant at every call site; the loops below make the result exact whatever the candidate)
+  uint16_t t = __half_as_ushort(__float2half_rn((float)(alpha + rhs * (1.0 / twoL))));
   for (int it = 0; it < 4 && pred(t); ++it) t = h_prev(t);
   for (int it = 0; it < 4 && !pred(h_next(t)); ++it) t = h_next(t);
   return t == 0x8000u ? (uint16_t)0 : t;     // -0 would break the sign test against +0
