@@ -61,6 +61,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fp16-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="override the batch (debugging only)")
+    ap.add_argument("--n-vis", type=int, default=0, help="override the visual tokens (debugging only)")
+    ap.add_argument("--n-text", type=int, default=-1, help="override the text tokens (debugging only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)",
@@ -84,6 +86,10 @@ def main() -> int:
     w = synth.WORKLOADS[args.config]
     if args.batch:
         w = w.replace(batch=args.batch)
+    if args.n_vis:
+        w = w.replace(n_vis=args.n_vis)
+    if args.n_text >= 0:
+        w = w.replace(n_text=args.n_text)
 
     def timed(fn, reps):
         """Median device time of fn over reps (HIP events on the current stream), in ms."""
@@ -345,7 +351,7 @@ def main() -> int:
     kernel_name = ("fused_row_kernel<%d> (the call's only launch)" % (min(k_group, 128) // 16) if fused
                    else "scores_kernel + pv_kernel + combine_kernel (all launches of one call)")
     traffic = None
-    if (fused and args.config == 2 and args.bits == 1 and args.group == 128 and not args.batch
+    if (fused and args.config == 2 and args.bits == 1 and args.group == 128 and not args.batch and not args.n_vis and args.n_text < 0
             and args.v_axis == "token"):
         # counter-derived HBM bytes per launch from the committed rocprofv3 summary of this command
         try:

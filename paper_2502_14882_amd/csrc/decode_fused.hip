@@ -176,6 +176,30 @@ __device__ inline float dpp_f32(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, true));
 }
 
+// Reductions over the 16 lanes of a row of the wave, on the DPP network; every lane of the row
+// ends up with the row's result.
+__device__ inline float row_min(float v) {
+  v = fminf(v, dpp_f32<0xB1>(v));     // quad_perm 1,0,3,2
+  v = fminf(v, dpp_f32<0x4E>(v));     // quad_perm 2,3,0,1
+  v = fminf(v, dpp_f32<0x141>(v));    // row_half_mirror
+  return fminf(v, dpp_f32<0x140>(v)); // row_mirror
+}
+__device__ inline float row_max(float v) {
+  v = fmaxf(v, dpp_f32<0xB1>(v));
+  v = fmaxf(v, dpp_f32<0x4E>(v));
+  v = fmaxf(v, dpp_f32<0x141>(v));
+  return fmaxf(v, dpp_f32<0x140>(v));
+}
+__device__ inline float row_sum(float v) {
+  v += dpp_f32<0xB1>(v);
+  v += dpp_f32<0x4E>(v);
+  v += dpp_f32<0x141>(v);
+  return v + dpp_f32<0x140>(v);
+}
+__device__ inline float lane_value(float v, int lane) {     // wave-uniform copy of one lane's value
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
 // Additive post-scaling term of one key group, sum_c q'[h][c] * min[c] for the four heads.  Every
 // lane brings two channels (q' already carries the softmax scale and the lane's operand weight
 // w, which inv_w = 1/w takes out again, per channel).  A transposing butterfly leaves lane (.., b1, b0) with head
@@ -628,16 +652,40 @@ fused_row_kernel(const FusedArgs a) {
     return;
   }
 
-  // ---- phase 2 set-up: calibration line and the softmax reference point, per head
+  // ---- phase 2 set-up: calibration line and the softmax reference point, per head.
+  // Every wave folds the per-wave extrema itself, spread over its lanes: lane 16h + w reads what
+  // wave w left for head h, a row reduction makes them the head's extrema.  With a split row the
+  // same lanes also fold the chunk extrema of the first pass (chunk w, w + 16, ...).
+  static_assert(kWaves <= 16 && kHeads == 4, "one row of 16 lanes per head");
+  float lo_l = FLT_MAX, hi_l = -FLT_MAX, tm_l = -FLT_MAX, glo_l = FLT_MAX, ghi_l = -FLT_MAX;
+  {
+    const int h = lane >> 4, w = lane & 15;
+    if (w < kVisWaves) {
+      lo_l = red[(w * kHeads + h) * kRedPerHead + 0];
+      hi_l = red[(w * kHeads + h) * kRedPerHead + 1];
+    } else if (w < kWaves) {
+      tm_l = red[(w * kHeads + h) * kRedPerHead + 2];
+    }
+    if (a.mode == kModePartial && a.calib_mode == CQ_CALIB_DYNAMIC && h < gh) {
+      const float* mm = a.ws_minmax + (head0 + h) * a.n_chunks * 2;
+      for (int cidx = w; cidx < a.n_chunks; cidx += 16) {
+        glo_l = fminf(glo_l, mm[2 * cidx]);
+        ghi_l = fmaxf(ghi_l, mm[2 * cidx + 1]);
+      }
+    }
+    lo_l = row_min(lo_l);
+    hi_l = row_max(hi_l);
+    tm_l = row_max(tm_l);
+    if (a.mode == kModePartial) {
+      glo_l = row_min(glo_l);
+      ghi_l = row_max(ghi_l);
+    }
+  }
   float a2[kHeads], c2v[kHeads], c2t[kHeads], mref[kHeads];
 #pragma unroll
   for (int h = 0; h < kHeads; ++h) {
-    float lo = FLT_MAX, hi = -FLT_MAX, tm = -FLT_MAX;
-    for (int w = 0; w < kVisWaves; ++w) {
-      lo = fminf(lo, red[(w * kHeads + h) * kRedPerHead + 0]);
-      hi = fmaxf(hi, red[(w * kHeads + h) * kRedPerHead + 1]);
-    }
-    for (int w = kVisWaves; w < kWaves; ++w) tm = fmaxf(tm, red[(w * kHeads + h) * kRedPerHead + 2]);
+    const float lo = lane_value(lo_l, 16 * h), hi = lane_value(hi_l, 16 * h);
+    const float tm = lane_value(tm_l, 16 * h);
     float slope = 1.f, gam = 0.f, shift = 0.f;    // s' = slope * (s - gam) + shift
     if (a.calib_mode != CQ_CALIB_NONE && nv > 0) {
       float glo = a.gamma, ghi = a.delta;
@@ -645,11 +693,8 @@ fused_row_kernel(const FusedArgs a) {
         glo = lo;
         ghi = hi;
         if (a.mode == kModePartial && h < gh) {   // extrema of the whole row, from the first pass
-          const float* mm = a.ws_minmax + (head0 + h) * a.n_chunks * 2;
-          for (int cidx = 0; cidx < a.n_chunks; ++cidx) {
-            glo = fminf(glo, mm[2 * cidx]);
-            ghi = fmaxf(ghi, mm[2 * cidx + 1]);
-          }
+          glo = fminf(glo, lane_value(glo_l, 16 * h));
+          ghi = fmaxf(ghi, lane_value(ghi_l, 16 * h));
         }
       }
       const float width = ghi - glo;
@@ -1148,12 +1193,17 @@ fused_row_kernel(const FusedArgs a) {
   if (tid < kHeads * kD) {
     const int h = tid / kD, c = tid % kD;
     if (h < gh) {
-      float num = 0.f, l = 0.f, m = 0.f;
-      for (int w = 0; w < kWaves; ++w) {
+      // the per-wave sums of the weights and of the additive value term: lane w of each row of 16
+      // lanes fetches wave w's, a row reduction adds them (a wave works on one head: 128 = 2 x 64)
+      const int wl = lane & 15;
+      float l = wl < kWaves ? red[(wl * kHeads + h) * kRedPerHead + 3] : 0.f;
+      float m = wl < kWaves ? red[(wl * kHeads + h) * kRedPerHead + 4] : 0.f;
+      l = row_sum(l);
+      m = row_sum(m);
+      float num = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w)
         num += reinterpret_cast<float*>(smem)[((size_t)w * kHeads + h) * kD + c];
-        l += red[(w * kHeads + h) * kRedPerHead + 3];
-        m += red[(w * kHeads + h) * kRedPerHead + 4];
-      }
       if (a.mode == kModeFull) {
         a.out[(head0 + h) * kD + c] = __float2half_rn((num + m) / l);
       } else {          // one (m, l, acc[d]) partial of the joint softmax per (head, chunk)
