@@ -361,6 +361,23 @@ fused_row_kernel(const FusedArgs a) {
   __syncthreads();   // red is reused below
   CQ_CLK(1);
 
+  // ring of the first value tiles of the narrow token-wise path (b <= 2): asked for during
+  // phase 1, right after the first key groups, so that phase 2 does not start on a cold load
+  constexpr bool kPrimeValues = !VCH && BITS <= 2;
+  v4i p2_cg[kRingV][BITS];
+  float p2_vsr[kRingV];
+  uint16_t p2_vmr[kRingV];       // raw fp16 bits: converting here would wait for the load at once
+  const uint32_t* p2_vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS);
+  auto p2_load_tile = [&](int slot, int jt) {
+    const int j0 = min(jt, nv - 64), j = j0 + lane;
+    // the tile's code bytes are contiguous: instruction e takes the e-th KB, whole cache lines
+#pragma unroll
+    for (int e = 0; e < BITS; ++e)
+      p2_cg[slot][e] = stream_load<kNtCodes>(reinterpret_cast<const v4i*>(p2_vc_row + (size_t)j0 * (4 * BITS) + 256 * e + 4 * lane));
+    p2_vsr[slot] = stream_load<NT>(vs_row + j);
+    p2_vmr[slot] = stream_load<NT>(vm_row + j);
+  };
+
   // =================================================================== phase 1: logits
   if (vis_wave) {
     // Lane roles on a visual wave:
@@ -528,6 +545,13 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
       for (int d = 0; d < kRK; ++d) load_group(d, wave + d * kVisWaves);
       pin_order();
+      if constexpr (kPrimeValues) {
+        if (a.mode != kModeExtrema) {
+#pragma unroll
+          for (int d = 0; d < kRingV; ++d) p2_load_tile(d, wave * 64 + d * (kVisWaves * 64));
+          pin_order();
+        }
+      }
       if constexpr (KW) {
         build_operand(0, stage, A0w, A1w, bias_w, inv_f_w, inv_f16_w);
         pin_order();
@@ -967,24 +991,14 @@ fused_row_kernel(const FusedArgs a) {
       // it, the integer accumulators are banked into fp32 before that tile is added
       int F_prep = 90, F_acc = 90, F_tile[2] = {90, 90};
       float fit_below = ldexpf(1.f, 29 - 90);   // scales below this fit the shift F_prep
-      const uint32_t* vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS);
       const int step = kVisWaves * 64;
-      const int last = nv - 64;                // first token of the row's last tile
       const int x_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;          // row of token lane
       const int x_rd = (kb * a.stride) * 4 + (n16 >> 1) * 16 + (n16 & 1) * 8;   // tr rows 16kb+k
       const int v_rd = (kb * 16 + (n16 >> 1)) * (16 * BITS) + (n16 & 1) * 8;
-      v4i cg[kRingV][BITS];
-      float vsr[kRingV];
-      uint16_t vmr[kRingV];       // raw fp16 bits: converting here would wait for the load at once
-      auto load_tile = [&](int slot, int jt) {
-        const int j0 = min(jt, last), j = j0 + lane;
-        // the tile's code bytes are contiguous: instruction e takes the e-th KB, whole cache lines
-#pragma unroll
-        for (int e = 0; e < BITS; ++e)
-          cg[slot][e] = stream_load<kNtCodes>(reinterpret_cast<const v4i*>(vc_row + (size_t)j0 * (4 * BITS) + 256 * e + 4 * lane));
-        vsr[slot] = stream_load<NT>(vs_row + j);
-        vmr[slot] = stream_load<NT>(vm_row + j);
-      };
+      auto& cg = p2_cg;
+      auto& vsr = p2_vsr;
+      auto& vmr = p2_vmr;
+      auto& load_tile = p2_load_tile;
       auto prep_tile = [&](int slot, int jt, int buf) {
         if (__builtin_amdgcn_ballot_w64(vsr[slot] >= fit_below) != 0) {
           // some token's scale does not fit the running shift (rare after the first tiles)
@@ -1014,9 +1028,7 @@ fused_row_kernel(const FusedArgs a) {
           *reinterpret_cast<v4i*>(stage + (BITS == 1 ? buf * 1024 : 0) + 1024 * e + 16 * lane) =
               cg[slot][e];
       };
-      const int j_first = wave * 64;
-#pragma unroll
-      for (int d = 0; d < kRingV; ++d) load_tile(d, j_first + d * step);
+      const int j_first = wave * 64;      // the ring's first tiles were asked for in phase 1
       if (j_first < nv) {
         prep_tile(0, j_first, 0);
         lds_publish();
