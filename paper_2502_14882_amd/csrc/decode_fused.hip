@@ -26,6 +26,7 @@
 
 #include <atomic>
 #include <cfloat>
+#include <type_traits>
 #include <cstdlib>
 
 #include "cq_internal.h"
@@ -1100,55 +1101,67 @@ fused_row_kernel(const FusedArgs a) {
     CQ_CLKW(48);
   } else {
     // text tail.  lane = (token slot kb, channels 8 * n16 .. +7): one 16-byte load covers 8 channels
-    // of one token, a wave-wide load covers 4 tokens.  The weights of a 64-token block are
-    // computed once (lane = token) and staged in the block's own logit slots.
+    // of one token, a wave-wide load covers 4 tokens.  The tail is handed to the text waves in
+    // shares of SH tokens; the weights of a share are computed once (lane = token) and staged in
+    // the share's own logit slots (SH / 4 slots of 16 bytes in each of the four head rows).
+    // Shares of 64 tokens are the efficient ones; a short tail (a split row's chunk, a small
+    // prompt) goes out in shares of 16 so that it still occupies all text waves.
     float tl[kHeads] = {0.f, 0.f, 0.f, 0.f};
     if (ntx > 0) {
       const __half* vt_row = a.v_text + ((size_t)row * a.n_text_cap + txt0) * kD + 8 * n16;
-      const int n_blocks = (ntx + 63) / 64;
-      const int p_wr = ((lane >> 4) * a.stride) * 4 + (lane & 15) * 16;
-      constexpr int kSteps = 16, kDepth = kRingTV;          // 16 wave-wide loads per block, 8 in flight
-      v8h ring[kDepth];
-      auto load_step = [&](int slot, int blk, int s) {
-        const int tok = min(min(blk, n_blocks - 1) * 64 + 4 * s + kb, ntx - 1);
-        ring[slot] = stream_load<NT>(reinterpret_cast<const v8h*>(vt_row + (size_t)tok * kD));
+      auto text_values = [&](auto share_tag) {
+        constexpr int SH = decltype(share_tag)::value, Q = SH / 4;
+        constexpr int kSteps = SH / 4, kDepth = kRingTV;     // wave-wide loads per share, in flight
+        static_assert(kSteps % kDepth == 0, "the ring divides a share");
+        const int n_sh = (ntx + SH - 1) / SH;
+        const int p_wr = ((lane / Q) * a.stride) * 4 + (lane % Q) * 16;
+        v8h ring[kDepth];
+        auto load_step = [&](int slot, int sh, int s) {
+          const int tok = min(min(sh, n_sh - 1) * SH + 4 * s + kb, ntx - 1);
+          ring[slot] = stream_load<NT>(reinterpret_cast<const v8h*>(vt_row + (size_t)tok * kD));
+        };
+#pragma unroll
+        for (int s = 0; s < kDepth; ++s) load_step(s, tw, s);
+        pin_order();
+        for (int sh = tw; sh < n_sh; sh += kTextWaves) {
+          const int t0 = sh * SH;
+          const int nt = min(SH, ntx - t0);
+          v4f pv = {0.f, 0.f, 0.f, 0.f};
+          if (lane < nt) {
+#pragma unroll
+            for (int h = 0; h < kHeads; ++h)
+              if (h < gh)
+                pv[h] = __builtin_amdgcn_exp2f(
+                    fmaf(logits[h * a.stride + nv + t0 + lane], kLog2e, c2t[h]));
+          }
+#pragma unroll
+          for (int h = 0; h < kHeads; ++h) tl[h] += pv[h];
+          uint8_t* pb = lbytes + (size_t)(nv + t0) * 4;
+          __builtin_amdgcn_wave_barrier();
+          if (lane < SH) *reinterpret_cast<v4f*>(pb + p_wr) = pv;          // zero beyond nt
+          lds_publish();
+#pragma unroll
+          for (int s = 0; s < kSteps; ++s) {
+            const int slot = s % kDepth;
+            const int l = 4 * s + kb;                       // token slot inside the share
+            const v4f pp = *reinterpret_cast<const v4f*>(pb + ((l / Q) * a.stride) * 4 + (l % Q) * 16);
+            const v8h raw = ring[slot];
+#pragma unroll
+            for (int h = 0; h < kHeads; ++h)
+#pragma unroll
+              for (int c = 0; c < 8; ++c) tacc[h][c] = fmaf(pp[h], (float)raw[c], tacc[h][c]);
+            // refill: step s + kDepth of this share, or the start of the wave's next share
+            if (s + kDepth < kSteps) load_step(slot, sh, s + kDepth);
+            else load_step(slot, sh + kTextWaves, s + kDepth - kSteps);
+            pin_order();
+          }
+        }
       };
-#pragma unroll
-      for (int s = 0; s < kDepth; ++s) load_step(s, tw, s);
-      pin_order();
-      for (int blk = tw; blk < n_blocks; blk += kTextWaves) {
-        const int t0 = blk * 64;
-        const int nt = min(64, ntx - t0);
-        v4f pv = {0.f, 0.f, 0.f, 0.f};
-        if (lane < nt) {
-#pragma unroll
-          for (int h = 0; h < kHeads; ++h)
-            if (h < gh)
-              pv[h] = __builtin_amdgcn_exp2f(
-                  fmaf(logits[h * a.stride + nv + t0 + lane], kLog2e, c2t[h]));
-        }
-#pragma unroll
-        for (int h = 0; h < kHeads; ++h) tl[h] += pv[h];
-        uint8_t* pb = lbytes + (size_t)(nv + t0) * 4;
-        __builtin_amdgcn_wave_barrier();
-        *reinterpret_cast<v4f*>(pb + p_wr) = pv;          // zero beyond nt
-        lds_publish();
-#pragma unroll
-        for (int s = 0; s < kSteps; ++s) {
-          const int slot = s % kDepth;
-          const int l = 4 * s + kb;                       // token slot inside the block
-          const v4f pp = *reinterpret_cast<const v4f*>(pb + ((l >> 4) * a.stride) * 4 + (l & 15) * 16);
-          const v8h raw = ring[slot];
-#pragma unroll
-          for (int h = 0; h < kHeads; ++h)
-#pragma unroll
-            for (int c = 0; c < 8; ++c) tacc[h][c] = fmaf(pp[h], (float)raw[c], tacc[h][c]);
-          // refill: step s + kDepth of this block, or the start of the wave's next block
-          if (s + kDepth < kSteps) load_step(slot, blk, s + kDepth);
-          else load_step(slot, blk + kTextWaves, s + kDepth - kSteps);
-          pin_order();
-        }
-      }
+      // rounds of shares over the text waves, a share of 16 costing ~1.1 quarters of one of 64
+      const int rounds64 = ((ntx + 63) / 64 + kTextWaves - 1) / kTextWaves;
+      const int rounds16 = ((ntx + 15) / 16 + kTextWaves - 1) / kTextWaves;
+      if (11 * rounds16 < 40 * rounds64) text_values(std::integral_constant<int, 16>{});
+      else text_values(std::integral_constant<int, 64>{});
       // fold the four token slots
 #pragma unroll
       for (int h = 0; h < kHeads; ++h)
