@@ -474,6 +474,24 @@ def test_tuned_wide_codes_on_split_and_full_length_rows(kernel_path, bits, monke
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("n_vis,n_text", [(6144, 100), (8192, 512), (10240, 0)])
+def test_long_whole_rows(kernel_path, bits, n_vis, n_text):
+    """Whole rows of 48 and more key groups run the kernel variant with three key groups in
+    flight per wave; short text tails take the 16-token value shares."""
+    if kernel_path != "auto":
+        pytest.skip("tuned kernels only")
+    w = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8, n_vis=n_vis, n_text=n_text,
+                                   seed=7100 + bits)
+    c = Case(w, H.layout_of(w, bits))
+    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+        c.check(cq.CQ_CALIB_NONE)
+    finally:
+        cq.cq_set_kernel_path(prev)
+
+
 def test_random_layouts_on_the_tuned_kernels(kernel_path, monkeypatch):
     """Seeded sweep over the layouts the tuned kernels accept: code width, group sizes, value
     axis, heads per KV head (1..8), ragged text tails, forced row splits, calibration modes."""
@@ -490,9 +508,13 @@ def test_random_layouts_on_the_tuned_kernels(kernel_path, monkeypatch):
             g = int(rng.integers(1, 9))
             hkv = int(rng.integers(1, 3))
             n_vis = 128 * int(rng.integers(1, 13))
+            if n_vis > 128 and trial % 4 == 3:          # statistics over the whole sequence
+                kg = n_vis
+                if vch:
+                    vg = n_vis
             n_text = int(rng.choice([0, 1, 15, 16, 17, 63, 64, 65, 130, 257]))
             chunks = int(rng.choice([1, 1, 2, 3]))
-            unit = max(128, vg if vch else 64, kg)
+            unit = max(128, min(vg, 128) if vch else 64, min(kg, 128))
             if n_vis // unit < chunks:
                 chunks = 1
             monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
