@@ -293,7 +293,9 @@ fused_row_kernel(const FusedArgs a) {
   // instruction up to b = 2 (wider value codes are read token by token in 16-byte pieces)
   constexpr bool kNtKeys = NT && BITS <= 4, kNtCodes = NT && BITS <= 2;
   static_assert(!KW || TILES == 8, "whole-sequence keys are processed 128 tokens at a time");
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the wave index as a scalar: what depends on the wave's role then branches and counts on the
+  // scalar unit (1.5 % of the whole kernel)
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   // workgroup = (row = b * Hkv + kvh, block of 4 query heads, chunk of the row's tokens)
   // Workgroups are handed to the 8 XCDs round-robin.  With two head blocks per KV head, the two
   // workgroups that read the same (row, chunk) get block indices 8 apart: same XCD, started
