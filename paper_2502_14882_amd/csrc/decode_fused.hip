@@ -198,6 +198,17 @@ __device__ inline float row_sum(float v) {
   v += dpp_f32<0x141>(v);
   return v + dpp_f32<0x140>(v);
 }
+// Sum over the wave's four rows of lanes, lane position by lane position (lane n of every row ends
+// up with v[n] + v[16 + n] + v[32 + n] + v[48 + n]): two lane swaps, no LDS.  Swapping a register
+// with its own copy hands every lane its partner's value.
+__device__ inline float rows_sum(float v) {
+  const unsigned x = __builtin_bit_cast(unsigned, v);
+  const auto h = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+  const float s = __builtin_bit_cast(float, (unsigned)h[0]) + __builtin_bit_cast(float, (unsigned)h[1]);
+  const unsigned y = __builtin_bit_cast(unsigned, s);
+  const auto q = __builtin_amdgcn_permlane16_swap(y, y, false, false);
+  return __builtin_bit_cast(float, (unsigned)q[0]) + __builtin_bit_cast(float, (unsigned)q[1]);
+}
 __device__ inline float lane_value(float v, int lane) {     // wave-uniform copy of one lane's value
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
@@ -1202,16 +1213,11 @@ fused_row_kernel(const FusedArgs a) {
       const int rounds16 = ((ntx + 15) / 16 + kTextWaves - 1) / kTextWaves;
       if (11 * rounds16 < 40 * rounds64) text_values(std::integral_constant<int, 16>{});
       else text_values(std::integral_constant<int, 64>{});
-      // fold the four token slots
+      // fold the four token slots (= the wave's four rows of lanes); every row ends up with the sum
 #pragma unroll
       for (int h = 0; h < kHeads; ++h)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          float v = tacc[h][c];
-          v += __shfl_xor(v, 16);
-          v += __shfl_xor(v, 32);
-          tacc[h][c] = v;
-        }
+        for (int c = 0; c < 8; ++c) tacc[h][c] = rows_sum(tacc[h][c]);
     }
 #pragma unroll
     for (int h = 0; h < kHeads; ++h) lsum[h] = tl[h];
@@ -1238,21 +1244,33 @@ fused_row_kernel(const FusedArgs a) {
     }
   } else if (kb == 0) {
 #pragma unroll
-    for (int h = 0; h < kHeads; ++h)
-#pragma unroll
-      for (int c = 0; c < 8; ++c) partial[h * kD + 8 * n16 + c] = tacc[h][c];
-  }
-#pragma unroll
-  for (int h = 0; h < kHeads; ++h) {
-    const float l = wave_sum(lsum[h]);
-    const float m = wave_sum(msum[h]);
-    if (lane == 0) {
-      red[(wave * kHeads + h) * kRedPerHead + 3] = l;
-      red[(wave * kHeads + h) * kRedPerHead + 4] = m;
-      if (wave == 0) red[h * kRedPerHead + 5] = mref[h];
+    for (int h = 0; h < kHeads; ++h) {
+      *reinterpret_cast<v4f*>(partial + h * kD + 8 * n16) = (v4f){tacc[h][0], tacc[h][1], tacc[h][2], tacc[h][3]};
+      *reinterpret_cast<v4f*>(partial + h * kD + 8 * n16 + 4) = (v4f){tacc[h][4], tacc[h][5], tacc[h][6], tacc[h][7]};
     }
   }
+  CQ_CLK(7);
+  // the per-wave sums of the weights and of the additive value term: eight independent reductions
+  // in one block, so they overlap (with a store between them they ran one after the other)
+  {
+    float ls[kHeads], ms[kHeads];
+#pragma unroll
+    for (int h = 0; h < kHeads; ++h) {
+      ls[h] = wave_sum(lsum[h]);
+      ms[h] = wave_sum(msum[h]);
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int h = 0; h < kHeads; ++h) {
+        red[(wave * kHeads + h) * kRedPerHead + 3] = ls[h];
+        red[(wave * kHeads + h) * kRedPerHead + 4] = ms[h];
+        if (wave == 0) red[h * kRedPerHead + 5] = mref[h];
+      }
+    }
+  }
+  CQ_CLK(8);
   __syncthreads();
+  CQ_CLK(9);
 
   // ---- epilogue: sum the waves, add the additive value term, normalise, round to fp16
   if (tid < kHeads * kD) {
