@@ -10,6 +10,7 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X")
+    config.addinivalue_line("markers", "tuned_only: runs once, on the tuned kernels (not on both kernel paths)")
 
 
 def _have_gpu() -> bool:

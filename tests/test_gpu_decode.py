@@ -17,7 +17,16 @@ import helpers as H
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["generic", "auto"], scope="module")
+def pytest_generate_tests(metafunc):
+    """Every case runs on both kernel paths, except the ones marked `tuned_only` (forced tuned
+    path, full sizes), which run once."""
+    if "kernel_path" in metafunc.fixturenames:
+        once = metafunc.definition.get_closest_marker("tuned_only") is not None
+        metafunc.parametrize("kernel_path", ["auto"] if once else ["generic", "auto"],
+                             indirect=True, scope="module")
+
+
+@pytest.fixture(autouse=True, scope="module")
 def kernel_path(request):
     """Every case runs twice: on the shape-agnostic kernels and on whatever AUTO selects
     (the tuned kernels where the layout allows)."""
@@ -154,11 +163,10 @@ def test_output_is_deterministic(cfg0):
     assert torch.equal(outs[0], outs[1])
 
 
+@pytest.mark.tuned_only
 def test_tuned_path_takes_the_benchmark_layouts(kernel_path):
     """The layouts of the decode workloads must not fall back silently: forcing the tuned path
     has to succeed (and agree with the oracle) for them."""
-    if kernel_path != "auto":
-        pytest.skip("runs once")
     cases = []
     for w in (synth.WORKLOADS[0],
               synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8),   # full-length rows
@@ -178,11 +186,10 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path):
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 def test_full_size_benchmark_config_on_sampled_rows(kernel_path):
     """configs[2] at full size, drawn on the GPU as bench.py does, through the kernel bench.py
     times; the oracle checks sampled (batch, KV head) rows, each one independently."""
-    if kernel_path != "auto":
-        pytest.skip("full size runs on the tuned kernels only")
     w = synth.WORKLOADS[2]
     lay = H.layout_of(w)
     x = synth.make_inputs(w, "cuda")
@@ -219,12 +226,11 @@ def test_full_size_benchmark_config_on_sampled_rows(kernel_path):
         assert err <= H.REL_L2_TOL, "row (%d,%d): rel L2 %.3e" % (b, h, err)
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("chunks", [1, 2, 5])
 def test_split_rows_agree_with_whole_rows(kernel_path, chunks, monkeypatch):
     """The tuned kernel on whole rows (one launch) and on rows split into chunks (extrema pass,
     partial pass, combine) must both match the oracle; g = 4 and g = 6 (two blocks of heads)."""
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
     monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
     prev = None
     cases = []
@@ -241,13 +247,12 @@ def test_split_rows_agree_with_whole_rows(kernel_path, chunks, monkeypatch):
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [1, 2])
 @pytest.mark.parametrize("kg,vg", [(128, 128), (128, 64), (64, 128), (32, 64), (32, 128)])
 def test_tuned_channelwise_values(kernel_path, bits, kg, vg):
     """Paper-literal value quantization (channel-wise over groups of tokens, Sec. 3.1) on the
     tuned kernels: whole rows, every calibration mode, g = 4 and g = 6."""
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
     cases = []
     for w in (synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=2304, n_text=200),
               synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=1280, n_text=70)):
@@ -262,15 +267,11 @@ def test_tuned_channelwise_values(kernel_path, bits, kg, vg):
         cq.cq_set_kernel_path(prev)
 
 
-@pytest.mark.parametrize("bits", [1, 2, 4, 8])
-@pytest.mark.parametrize("v_whole", [False, True])
+@pytest.mark.tuned_only
+@pytest.mark.parametrize("bits,v_whole", [(1, False), (2, False), (4, False), (8, False), (1, True), (2, True)])
 def test_tuned_whole_sequence_statistics(kernel_path, bits, v_whole, monkeypatch):
     """Sec. 3.1 as printed: one (scale, min) pair per channel over ALL visual tokens, for keys and
     (v_whole) for values too, on the tuned kernels; whole rows and rows split into chunks."""
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
-    if v_whole and bits > 2:
-        pytest.skip("wide codes: token-wise values only on the tuned kernels")
     cases = []
     for w in (synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=2304, n_text=200),
               synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=1280, n_text=70)):
@@ -289,10 +290,9 @@ def test_tuned_whole_sequence_statistics(kernel_path, bits, v_whole, monkeypatch
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("chunks", [2, 3])
 def test_tuned_channelwise_values_on_split_rows(kernel_path, chunks, monkeypatch):
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
     monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
     cases = []
     for kg, vg in ((128, 128), (32, 128), (64, 64)):
@@ -307,10 +307,9 @@ def test_tuned_channelwise_values_on_split_rows(kernel_path, chunks, monkeypatch
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 def test_full_length_row_with_channelwise_values(kernel_path):
     """configs[2]-length rows (8192 + 512 tokens) with channel-wise values, tuned kernels."""
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
     w = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8)
     c = Case(w, H.layout_of(w, 1, 128, 128, 0, 0))
     prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
@@ -320,13 +319,12 @@ def test_full_length_row_with_channelwise_values(kernel_path):
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("chunks", [1, 3])
 def test_decode_replayed_from_a_hip_graph(kernel_path, chunks, monkeypatch):
     """cq_decode_attn allocates nothing and blocks on nothing, so a serving loop can record it
     into a HIP graph: every replay, with eager work and synchronisations in between, must
     reproduce the eager result bit for bit (whole rows and split rows)."""
-    if kernel_path != "auto":
-        pytest.skip("runs once")
     monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
     w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200)
     c = Case(w, H.layout_of(w))
@@ -364,13 +362,12 @@ def test_decode_replayed_from_a_hip_graph(kernel_path, chunks, monkeypatch):
             assert torch.equal(got, want), "replay %d differs from the eager result" % rep
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [1, 2])
 def test_full_size_long_context_config_on_sampled_rows(kernel_path, bits):
     """configs[4] at full size (batch 8, g = 6, 65536 + 1024 tokens) through the launches bench.py
     times (rows split into chunks, two head blocks, extrema + partial + combine); the oracle
     checks sampled (batch, KV head) rows, each one independently."""
-    if kernel_path != "auto":
-        pytest.skip("full size runs on the tuned kernels only")
     w = synth.WORKLOADS[4]
     lay = H.layout_of(w, bits)
     x = synth.make_inputs(w, "cuda")
@@ -435,13 +432,12 @@ def test_decoding_several_steps_with_a_growing_text_tail(kernel_path):
         assert torch.equal(k_dev.cpu(), k_tail) and torch.equal(v_dev.cpu(), v_tail)
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("kg", [32, 64, 128])
 def test_tuned_wide_codes(kernel_path, bits, kg):
     """4- and 8-bit codes on the tuned kernels (nibbles and bytes as matrix operands, the
     offset of the 8-bit operand carried by the additive terms): g = 4 and g = 6, every mode."""
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
     cases = []
     for w in (synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1536, n_text=200),
               synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=1280, n_text=70)):
@@ -456,10 +452,9 @@ def test_tuned_wide_codes(kernel_path, bits, kg):
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [4, 8])
 def test_tuned_wide_codes_on_split_and_full_length_rows(kernel_path, bits, monkeypatch):
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
     w_full = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8)
     full = Case(w_full, H.layout_of(w_full, bits))
     w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200)
@@ -474,13 +469,12 @@ def test_tuned_wide_codes_on_split_and_full_length_rows(kernel_path, bits, monke
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [1, 2])
 @pytest.mark.parametrize("n_vis,n_text", [(6144, 100), (8192, 512), (10240, 0)])
 def test_long_whole_rows(kernel_path, bits, n_vis, n_text):
     """Whole rows of 48 and more key groups run the kernel variant with three key groups in
     flight per wave; short text tails take the 16-token value shares."""
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
     w = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8, n_vis=n_vis, n_text=n_text,
                                    seed=7100 + bits)
     c = Case(w, H.layout_of(w, bits))
@@ -492,11 +486,10 @@ def test_long_whole_rows(kernel_path, bits, n_vis, n_text):
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 def test_random_layouts_on_the_tuned_kernels(kernel_path, monkeypatch):
     """Seeded sweep over the layouts the tuned kernels accept: code width, group sizes, value
     axis, heads per KV head (1..8), ragged text tails, forced row splits, calibration modes."""
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
     rng = np.random.default_rng(2024)
     prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
     try:

@@ -11,7 +11,16 @@ import helpers as H
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["generic", "auto"], scope="module")
+def pytest_generate_tests(metafunc):
+    """Every case runs on both kernel paths, except the ones marked `tuned_only` (forced tuned
+    path, full sizes), which run once."""
+    if "kernel_path" in metafunc.fixturenames:
+        once = metafunc.definition.get_closest_marker("tuned_only") is not None
+        metafunc.parametrize("kernel_path", ["auto"] if once else ["generic", "auto"],
+                             indirect=True, scope="module")
+
+
+@pytest.fixture(autouse=True, scope="module")
 def kernel_path(request):
     """Every case runs on the shape-agnostic kernels and on whatever AUTO selects."""
     prev = cq.cq_set_kernel_path({"generic": cq.CQ_PATH_GENERIC, "auto": cq.CQ_PATH_AUTO}[request.param])
@@ -117,13 +126,12 @@ def test_runs_on_a_side_stream():
     H.assert_qtensor_equal(v_out, vq, "side stream values")
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [1, 2, 4, 8])
 @pytest.mark.parametrize("group", [32, 64, 128])
 def test_tuned_path_takes_the_benchmark_layouts(kernel_path, bits, group):
     """head_dim 128, b in {1,2}, groups 32/64/128 must run on the tuned kernels (no silent
     fallback) and stay bit-exact, including exact ties and heavy-tailed outliers."""
-    if kernel_path != "auto":
-        pytest.skip("runs once")
     prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         w = synth.WORKLOADS[4].replace(batch=2, n_kv_heads=2, n_q_heads=2, n_vis=1024)
@@ -139,14 +147,13 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path, bits, group):
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [1, 2, 4, 8])
 @pytest.mark.parametrize("n_vis", [256, 640, 2304])
 def test_tuned_whole_sequence_statistics(kernel_path, bits, n_vis):
     """Sec. 3.1 as printed (one pair per channel over all tokens, keys and values) on the tuned
     kernels: extrema pass + tile pass, with exact ties, a constant channel, signed zeros and rows
     whose extreme elements sit in the first and in the last tile."""
-    if kernel_path != "auto":
-        pytest.skip("runs once")
     prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         w = synth.WORKLOADS[4].replace(batch=2, n_kv_heads=2, n_q_heads=2, n_vis=n_vis)
@@ -165,13 +172,12 @@ def test_tuned_whole_sequence_statistics(kernel_path, bits, n_vis):
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits,group", [(1, 128), (2, 32), (4, 64), (8, 128)])
 def test_full_size_quantizer_config_on_sampled_rows(kernel_path, bits, group):
     """configs[3] at full size (batch 128, 8 KV heads, 16384 tokens), drawn on the GPU as
     bench.py does and quantized by the launch bench.py times; the oracle checks sampled
     (batch, KV head) rows bit for bit, each one independently (rows do not interact)."""
-    if kernel_path != "auto":
-        pytest.skip("full size runs on the tuned kernels only")
     from oracle import cq_oracle as O
     w = synth.WORKLOADS[3]
     lay = H.layout_of(w, bits, group, group)
@@ -194,12 +200,11 @@ def test_full_size_quantizer_config_on_sampled_rows(kernel_path, bits, group):
             H.assert_qtensor_equal(got, ref, "configs[3] %s row (%d,%d)" % (name, b, h))
 
 
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [4, 8])
 def test_wide_codes_round_exact_ties_to_even_on_the_tuned_path(kernel_path, bits):
     """Every code boundary of a 4- or 8-bit grid hit exactly: values k + 1/2 steps of a group
     whose range makes the step a power of two, on both axes."""
-    if kernel_path != "auto":
-        pytest.skip("runs once")
     L = (1 << bits) - 1
     w = synth.WORKLOADS[1].replace(batch=1, n_kv_heads=1, n_q_heads=1, n_vis=512)
     x = synth.make_inputs(w, "cpu", parts=("k", "v"))
@@ -219,11 +224,10 @@ def test_wide_codes_round_exact_ties_to_even_on_the_tuned_path(kernel_path, bits
         cq.cq_set_kernel_path(prev)
 
 
+@pytest.mark.tuned_only
 def test_random_layouts_on_the_tuned_quantizer(kernel_path):
     """Seeded sweep over what the tuned quantizer accepts: code width, group size, either axis for
     keys and values, row counts and lengths; heavy-tailed and outlier inputs; bit-exact."""
-    if kernel_path != "auto":
-        pytest.skip("tuned kernels only")
     rng = np.random.default_rng(99)
     prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
