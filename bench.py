@@ -121,11 +121,20 @@ def main() -> int:
                                 max(5, args.steps // 10))
                 nbytes = rows * w.n_vis * (2 * w.head_dim * 2 + 2 * w.head_dim * bits / 8
                                            + 6.0 * w.head_dim / group * 2)
+                # the same reads and writes without the arithmetic: what this traffic costs on this machine
+                n_tiles = rows * w.n_vis // 128
+                cb, mb = 2048 * bits, 768 * 128 // group
+                sc_c = torch.empty(n_tiles * cb, dtype=torch.uint8, device=dev)
+                sc_m = torch.empty(n_tiles * mb, dtype=torch.uint8, device=dev)
+                tr_med, _ = timed(lambda: (cq.cq_bench_tile_traffic(x["k"], sc_c, sc_m, n_tiles, cb, mb),
+                                           cq.cq_bench_tile_traffic(x["v"], sc_c, sc_m, n_tiles, cb, mb)), 10)
                 sweep.append({"bits": bits, "group": group, "ms": med, "min_ms": mn,
                               "bytes_read_plus_written": nbytes,
                               "GB/s": nbytes / (med * 1e-3) / 1e9,
-                              "frac_of_hbm_peak": nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS})
-                del k_q, v_q
+                              "frac_of_hbm_peak": nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                              "same_traffic_without_arithmetic_ms": tr_med,
+                              "quantizer_vs_traffic_only": tr_med / med})
+                del k_q, v_q, sc_c, sc_m
         # practical ceiling: plain streaming reads of the same two input tensors
         in_bytes = x["k"].numel() * 2
         rd_ms, _ = timed(lambda: (cq.cq_bench_stream_read(x["k"], in_bytes),

@@ -197,6 +197,15 @@ int cq_bench_stream_read(const void *buf, size_t bytes, void *sink, void *stream
 /* Measurement aid: plain device-to-device copy of `bytes` bytes (both 16-byte aligned); the
  * kernel of known traffic that hardware byte counters are scaled with. */
 int cq_bench_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
+/* Measurement aid: the memory traffic of the tuned quantizer without its arithmetic.  One block per
+ * tile of 128 tokens x 128 fp16 values reads the tile's 32 KB of `x_f16` (device, n_tiles * 32 KB,
+ * 16-byte aligned) with the quantizer's load pattern and writes `code_bytes_per_tile` (a multiple
+ * of 16) to `codes` (device, 16-byte aligned) and `meta_bytes_per_tile` (a multiple of 4) to `meta`
+ * (device, 4-byte aligned), both tile after tile.  What is written is meaningless.  CQ_ERR_NULL for
+ * null pointers, CQ_ERR_ALIGN for misaligned ones, CQ_ERR_SHAPE for sizes that are not such
+ * multiples. */
+int cq_bench_tile_traffic(const void *x_f16, void *codes, void *meta, size_t n_tiles,
+                          int code_bytes_per_tile, int meta_bytes_per_tile, void *stream);
 
 /* Text for a cq_status value; never NULL. */
 const char *cq_status_string(int status);

@@ -77,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.cq_bench_stream_read.argtypes = [V, ctypes.c_size_t, V, V]
         L.cq_bench_stream_copy.restype = ctypes.c_int
         L.cq_bench_stream_copy.argtypes = [V, V, ctypes.c_size_t, V]
+        L.cq_bench_tile_traffic.restype = ctypes.c_int
+        L.cq_bench_tile_traffic.argtypes = [V, V, V, ctypes.c_size_t, ctypes.c_int, ctypes.c_int, V]
         L.cq_status_string.restype = ctypes.c_char_p
         L.cq_status_string.argtypes = [ctypes.c_int]
         L.cq_last_error.restype = ctypes.c_char_p
@@ -238,6 +240,17 @@ def cq_bench_stream_read(buf: torch.Tensor, nbytes: int) -> None:
     """Measurement aid: enqueue a plain streaming read of the first nbytes of buf."""
     assert nbytes <= buf.numel() * buf.element_size()
     _check(lib().cq_bench_stream_read(buf.data_ptr(), int(nbytes), None, _stream(buf)))
+
+
+def cq_bench_tile_traffic(x: torch.Tensor, codes: torch.Tensor, meta: torch.Tensor, n_tiles: int,
+                          code_bytes_per_tile: int, meta_bytes_per_tile: int) -> None:
+    """The tuned quantizer's memory traffic without its arithmetic (measurement aid)."""
+    assert x.is_cuda and codes.is_cuda and meta.is_cuda
+    assert x.numel() * x.element_size() >= n_tiles * 32768
+    assert codes.numel() * codes.element_size() >= n_tiles * code_bytes_per_tile
+    assert meta.numel() * meta.element_size() >= n_tiles * meta_bytes_per_tile
+    _check(lib().cq_bench_tile_traffic(x.data_ptr(), codes.data_ptr(), meta.data_ptr(), int(n_tiles),
+                                       int(code_bytes_per_tile), int(meta_bytes_per_tile), _stream(x)))
 
 
 def cq_bench_stream_copy(dst: torch.Tensor, src: torch.Tensor, nbytes: int) -> None:
