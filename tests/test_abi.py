@@ -133,6 +133,19 @@ def test_tau_search_argument_errors():
     assert call(lay=cq.make_layout(2, 8, 2, 128, 0)) == cq.CQ_ERR_SHAPE    # nothing quantized
 
 
+def test_measurement_aid_argument_errors():
+    """The traffic skeleton of the quantizer rejects what it cannot run before any launch."""
+    L = cq.lib()
+    f = L.cq_bench_tile_traffic
+    assert f(None, FAKE, FAKE, 4, 2048, 768, None) == cq.CQ_ERR_NULL
+    assert f(FAKE, None, FAKE, 4, 2048, 768, None) == cq.CQ_ERR_NULL
+    assert f(FAKE + 8, FAKE, FAKE, 4, 2048, 768, None) == cq.CQ_ERR_ALIGN
+    assert f(FAKE, FAKE, FAKE + 2, 4, 2048, 768, None) == cq.CQ_ERR_ALIGN
+    assert f(FAKE, FAKE, FAKE, 4, 2040, 768, None) == cq.CQ_ERR_SHAPE
+    assert f(FAKE, FAKE, FAKE, 4, 2048, 770, None) == cq.CQ_ERR_SHAPE
+    assert f(FAKE, FAKE, FAKE, 0, 2048, 768, None) == cq.CQ_OK          # nothing to do, no launch
+
+
 def test_workspace_size_rule():
     lay = cq.make_layout(2, 8, 2, 128, 1024)
     n = cq.cq_decode_workspace_bytes(lay, 32)
