@@ -866,7 +866,33 @@ fused_row_kernel(const FusedArgs a) {
       };
       v4i acc_w = {0, 0, 0, 0};
       const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
-      auto m_step = [&](int k, int d) {
+      // folds the finished value group into fp32 and asks for the parameters of group `next_group`
+      auto fold_group = [&](int next_group) {
+        const float wsum = digits_to_float(acc_w);
+        acc_w = (v4i){0, 0, 0, 0};
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+          // accumulator p holds channel c_lo + 7 - p (b = 1), c_lo + 3 - p or c_hi + 3 - (p - 4)
+          const int i = 7 - p;
+          const int vec = BITS == 1 ? i >> 2 : p >> 2, el = BITS == 1 ? i & 3 : 3 - (p & 3);
+          const uint32_t mpair = (uint32_t)gmn[vec][el >> 1];
+          const float mn = __half2float(__ushort_as_half((uint16_t)((el & 1) ? mpair >> 16 : mpair & 0xffffu)));
+          // the operand byte of a set code is 2^p (b = 1) resp. code * {1, 4, 16, 16}: take that out
+          const float sc = gsc[vec][el] * variant_weight<BITS>(p % (8 / BITS));
+          facc[p] = fmaf(digits_to_float(acc[p]), sc, fmaf(wsum, mn, facc[p]));
+          acc[p] = (v4i){0, 0, 0, 0};
+        }
+        pin_order();
+        load_group(next_group);
+        pin_order();
+      };
+      // FOLD: the tile ends a value group, whose sums are folded into fp32 and whose successor's
+      // parameters are asked for.  It is a compile-time property of the call site, so that every
+      // step issues the same loads whatever happens at run time: with a branch around loads the
+      // compiler drained all outstanding loads in every step (`s_waitcnt vmcnt(0)`), which took the
+      // ring of value tiles out of flight.
+      auto m_step = [&](int k, int d, auto fold_tag) {
+        constexpr bool FOLD = decltype(fold_tag)::value;
         const int buf = d & 1;
         const int jt = tile_start(k);
         const uint8_t* xr = lbytes + (size_t)jt * 4 + x_rd;
@@ -900,29 +926,7 @@ fused_row_kernel(const FusedArgs a) {
           acc[p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, B, acc[p], 0, 0, 0);
         }
         acc_w = __builtin_amdgcn_mfma_i32_16x16x64_i8(A, ones, acc_w, 0, 0, 0);
-        // last tile of a value group: fold it into fp32.  With whole-sequence statistics every
-        // group has the row's parameters, so the wave folds once, after its last tile (an int32
-        // accumulator takes 2^20 per tile at most: 2047 tiles, a workgroup's LDS holds ~140)
-        const bool fold = a.v_pstride == 0 ? k == n_my - 1 : (k & (tpg - 1)) == tpg - 1;
-        if (fold) {
-          const float wsum = digits_to_float(acc_w);
-          acc_w = (v4i){0, 0, 0, 0};
-#pragma unroll
-          for (int p = 0; p < 8; ++p) {
-            // accumulator p holds channel c_lo + 7 - p (b = 1), c_lo + 3 - p or c_hi + 3 - (p - 4)
-            const int i = 7 - p;
-            const int vec = BITS == 1 ? i >> 2 : p >> 2, el = BITS == 1 ? i & 3 : 3 - (p & 3);
-            const uint32_t mpair = (uint32_t)gmn[vec][el >> 1];
-            const float mn = __half2float(__ushort_as_half((uint16_t)((el & 1) ? mpair >> 16 : mpair & 0xffffu)));
-            // the operand byte of a set code is 2^p (b = 1) resp. code * {1, 4, 16, 16}: take that out
-            const float sc = gsc[vec][el] * variant_weight<BITS>(p % (8 / BITS));
-            facc[p] = fmaf(digits_to_float(acc[p]), sc, fmaf(wsum, mn, facc[p]));
-            acc[p] = (v4i){0, 0, 0, 0};
-          }
-          pin_order();
-          load_group((k >> tsh) + 1);
-          pin_order();
-        }
+        if constexpr (FOLD) fold_group((k >> tsh) + 1);
         lds_publish();
       };
       if (n_my > 0) {
@@ -933,10 +937,32 @@ fused_row_kernel(const FusedArgs a) {
         lds_publish();
         load_tile(0, kRingV);
         pin_order();
-        for (int k = 0; k < n_my; k += kRingV) {
-#pragma unroll
-          for (int d = 0; d < kRingV; ++d)
-            if (k + d < n_my) m_step(k + d, d);
+        static_assert(kRingV == 2, "the loops below pair a ring slot with a tile of a 128-token group");
+        const std::integral_constant<bool, true> fold_yes;
+        const std::integral_constant<bool, false> fold_no;
+        if (a.v_pstride == 0) {
+          // whole-sequence statistics: every group has the row's parameters, so the wave folds
+          // once, after its last tile (an int32 accumulator takes 2^20 per tile at most: 2047
+          // tiles, a workgroup's LDS holds ~140)
+          int k = 0;
+          for (; k + 2 <= n_my; k += 2) {
+            m_step(k, 0, fold_no);
+            m_step(k + 1, 1, fold_no);
+          }
+          if (k < n_my) m_step(k, 0, fold_no);
+          fold_group(0);
+        } else if (tpg == 2) {              // groups of 128 tokens: two tiles, the second one folds
+          for (int k = 0; k < n_my; k += 2) {
+            m_step(k, 0, fold_no);
+            m_step(k + 1, 1, fold_yes);
+          }
+        } else {                            // groups of 64 tokens: every tile folds
+          int k = 0;
+          for (; k + 2 <= n_my; k += 2) {
+            m_step(k, 0, fold_yes);
+            m_step(k + 1, 1, fold_yes);
+          }
+          if (k < n_my) m_step(k, 0, fold_yes);
         }
       }
       Fv = 0;
@@ -1162,7 +1188,8 @@ fused_row_kernel(const FusedArgs a) {
       const __half* vt_row = a.v_text + ((size_t)row * a.n_text_cap + txt0) * kD + 8 * n16;
       auto text_values = [&](auto share_tag) {
         constexpr int SH = decltype(share_tag)::value, Q = SH / 4;
-        constexpr int kSteps = SH / 4, kDepth = kRingTV;     // wave-wide loads per share, in flight
+        // wave-wide loads per share, and how many of them are in flight
+        constexpr int kSteps = SH / 4, kDepth = kRingTV < kSteps ? kRingTV : kSteps;
         static_assert(kSteps % kDepth == 0, "the ring divides a share");
         const int n_sh = (ntx + SH - 1) / SH;
         const int p_wr = ((lane / Q) * a.stride) * 4 + (lane % Q) * 16;
