@@ -1085,7 +1085,11 @@ fused_row_kernel(const FusedArgs a) {
         }
         F_tile[buf] = F_prep;
         const float vsf = ldexpf(vsr[slot], F_prep);
-        const float vmf = __half2float(__ushort_as_half(vmr[slot]));
+        // converted here and now: folded into the multiply-adds below, the raw 16 bits would stay
+        // live past the ring's next load into this slot, the compiler would give that load another
+        // register and copy it back at the loop's end - behind a wait for every outstanding load
+        float vmf = __half2float(__ushort_as_half(vmr[slot]));
+        asm volatile("" : "+v"(vmf));
         float lg[kHeads];
 #pragma unroll
         for (int h = 0; h < kHeads; ++h) lg[h] = logits[h * a.stride + jt + lane];
