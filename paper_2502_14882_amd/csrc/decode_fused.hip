@@ -1050,10 +1050,12 @@ fused_row_kernel(const FusedArgs a) {
       load_tile(0, j_first);
       load_tile(1, j_first + step);
       pin_order();
-      for (int j0 = j_first; j0 < nv; j0 += 2 * step) {
+      int j0 = j_first;
+      for (; j0 + step < nv; j0 += 2 * step) {        // no branch around the ring's loads in here
         tile_step(j0, 0);
-        if (j0 + step < nv) tile_step(j0 + step, 1);
+        tile_step(j0 + step, 1);
       }
+      if (j0 < nv) tile_step(j0, 0);
       Fv = F_acc;
     } }
     if constexpr (!VCH && BITS <= 2) { if (nv > 0) {
