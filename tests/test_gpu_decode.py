@@ -186,12 +186,23 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path):
         cq.cq_set_kernel_path(prev)
 
 
+# the layouts that bench.py times on configs[2]: (bits, key group, value axis, value group); a group
+# of 0 stands for the whole sequence
+FULL_SIZE_LAYOUTS = [(1, 128, 1, 128), (2, 128, 1, 128), (4, 128, 1, 128), (8, 128, 1, 128),
+                     (1, 32, 1, 128), (1, 64, 1, 128), (1, 128, 0, 128), (2, 128, 0, 128),
+                     (1, 0, 1, 128), (1, 0, 0, 0), (2, 0, 0, 0)]
+
+
 @pytest.mark.tuned_only
-def test_full_size_benchmark_config_on_sampled_rows(kernel_path):
-    """configs[2] at full size, drawn on the GPU as bench.py does, through the kernel bench.py
-    times; the oracle checks sampled (batch, KV head) rows, each one independently."""
+@pytest.mark.parametrize("bits,k_group,v_axis,v_group", FULL_SIZE_LAYOUTS)
+def test_full_size_benchmark_config_on_sampled_rows(kernel_path, bits, k_group, v_axis, v_group):
+    """configs[2] at full size, drawn on the GPU as bench.py does, through the kernels bench.py
+    times (every layout of its command line); the oracle checks sampled (batch, KV head) rows,
+    each one independently."""
     w = synth.WORKLOADS[2]
-    lay = H.layout_of(w)
+    k_group = k_group or w.n_vis
+    v_group = v_group or w.n_vis
+    lay = H.layout_of(w, bits, k_group, v_group, 0, v_axis)
     x = synth.make_inputs(w, "cuda")
     k_dev, v_dev = cq.cq_quantize_kv(lay, x["k"], x["v"])
     prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
@@ -204,13 +215,13 @@ def test_full_size_benchmark_config_on_sampled_rows(kernel_path):
     g = w.n_q_heads // w.n_kv_heads
     rng = np.random.default_rng(5)
     rows = {(0, 0), (w.batch - 1, w.n_kv_heads - 1)}
-    while len(rows) < 6:
+    while len(rows) < (6 if (bits, k_group, v_axis) == (1, 128, 1) else 3):
         rows.add((int(rng.integers(w.batch)), int(rng.integers(w.n_kv_heads))))
     for b, h in sorted(rows):
         k_row = x["k"][b:b + 1, h:h + 1].cpu().numpy()
         v_row = x["v"][b:b + 1, h:h + 1].cpu().numpy()
-        kq = O.quantize_tensor(k_row, 1, O.AXIS_CHANNEL, 128)
-        vq = O.quantize_tensor(v_row, 1, O.AXIS_TOKEN, 128)
+        kq = O.quantize_tensor(k_row, bits, O.AXIS_CHANNEL, k_group)
+        vq = O.quantize_tensor(v_row, bits, v_axis, v_group)
         assert np.array_equal(H.words_of(k_dev.codes[b:b + 1, h:h + 1]), kq["words"])
         assert np.array_equal(H.words_of(v_dev.codes[b:b + 1, h:h + 1]), vq["words"])
         assert np.array_equal(k_dev.scale[b:b + 1, h:h + 1].cpu().numpy().view(np.uint32),
