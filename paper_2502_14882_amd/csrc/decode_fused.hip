@@ -1,4 +1,4 @@
-// Fused decode attention over the packed 1- or 2-bit cache for head_dim 128 (gfx950).
+// Fused decode attention over the packed cache (1, 2, 4 or 8 bits) for head_dim 128 (gfx950).
 //
 // One workgroup owns one (batch, KV head) row: all of its g query heads, every visual token and
 // the text tail.  The raw logits of the row live in LDS, so the dynamic calibration of Sec. 3.2
@@ -22,6 +22,11 @@
 // Work split inside the workgroup (12 waves): waves 0..7 stream the packed visual cache, waves
 // 8..11 stream the fp16 text tail at the same time, so the bandwidth-heavy text reads overlap the
 // compute-heavy visual phases.  Every stream keeps a ring of loads several tiles deep in flight.
+// Two rules keep those rings in flight (the compiler's wait counting is exact only in straight
+// code): the steady-state loops have no branch around a global load (clamped addresses, tails
+// apart, group ends known at compile time), and nothing keeps a loaded register alive past the
+// ring's next load into it (values are converted when they are used first).  Broken, either rule
+// costs an `s_waitcnt vmcnt(0)` per iteration.
 #include <hip/hip_fp16.h>
 
 #include <atomic>
