@@ -356,8 +356,11 @@ fused_row_kernel(const FusedArgs a) {
   off += (size_t)kVisWaves * kStageBytes;
   float* red = reinterpret_cast<float*>(smem + off);   // [kWaves][kHeads][kRedPerHead]
 
-  // rows of unused heads (g < 4) are computed along but never output; keep them finite
-  for (int i = gh * a.stride + tid; i < kHeads * a.stride; i += kThreads) logits[i] = 0.f;
+  // rows of unused heads (g < 4) are computed along but never output; keep them finite.  Their
+  // visual slots are written in phase 1 like everyone's (their query is zero, so are their
+  // logits); only the text slots and the padding behind them are never written by anyone.
+  for (int h = gh; h < kHeads; ++h)
+    for (int i = nv + tid; i < a.stride; i += kThreads) logits[h * a.stride + i] = 0.f;
 
   // ---- phase 0: query to LDS and max |q| per head.  The fixed-point shifts and the additive
   // post-scaling term q . min_t are formed on the fly in phases 1 and 2 from the scales and minima
