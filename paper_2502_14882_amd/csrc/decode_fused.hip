@@ -81,6 +81,10 @@ constexpr float kLog2e = 1.4426950408889634f;
 // writes one online-softmax partial per (head, chunk) for the combine kernel.
 enum { kModeFull = 0, kModeExtrema = 1, kModePartial = 2 };
 
+// First unit of chunk c when n = base * n_chunks + rem units are dealt to n_chunks chunks, the
+// first rem of them taking base + 1 (host and device share the rule).
+__host__ __device__ inline int chunk_first(int base, int rem, int c) { return c * base + (c < rem ? c : rem); }
+
 struct FusedArgs {
   const __half* q;
   const uint32_t* k_codes; const float* k_scale; const uint16_t* k_min;
@@ -99,6 +103,9 @@ struct FusedArgs {
   int stride;        // floats between the logit rows of two heads in LDS
   int mode, n_chunks, nhb;   // kMode*, chunks per row, blocks of 4 query heads per KV head
   int n_pieces;              // rows * n_chunks
+  unsigned chunks_magic;     // fl(2^32 / n_chunks) + 1, or 0 when n_chunks == 1
+  int units_base, units_rem;       // units of visual tokens per chunk: quotient and remainder
+  int tblocks_base, tblocks_rem;   // 64-token text blocks per chunk, likewise
   float* ws_minmax;  // split rows: [B*Hq][n_chunks][2] extrema of the visual logits
   float* ws_partial; // split rows: [B*Hq][n_chunks][d + 2] partials (m, l, acc) for the combine
   int calib_mode; float tau1, tau2, gamma, delta, softmax_scale;
@@ -317,27 +324,30 @@ fused_row_kernel(const FusedArgs a) {
   // Workgroups are handed to the 8 XCDs round-robin.  With two head blocks per KV head, the two
   // workgroups that read the same (row, chunk) get block indices 8 apart: same XCD, started
   // together, so the second one's key/value reads are served by that XCD's L2.
+  // None of this divides: a division by a value that is only known at run time is emulated with
+  // dozens of scalar instructions and several round trips through the vector unit, and the eight of
+  // them that stood here ran (on every wave) before the first load of a workgroup could be issued.
   int piece = blockIdx.x, hb = 0;           // piece = row * n_chunks + chunk
-  if (a.nhb > 1) {
-    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-    hb = slot % a.nhb;
-    piece = (slot / a.nhb) * 8 + xcd;
+  if (a.nhb > 1) {                          // nhb = 2: slot = block / 8, hb = slot % 2
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    hb = slot & 1;
+    piece = (slot >> 1) * 8 + xcd;
     if (piece >= a.n_pieces) return;        // grid is rounded up to whole groups of 8 pieces
   }
-  const int chunk = piece % a.n_chunks, row = piece / a.n_chunks;
-  const int b = row / a.Hkv, kvh = row % a.Hkv;
+  // row = piece / n_chunks by multiplication with the host's fl(2^32 / n_chunks) + 1 (exact while
+  // piece * n_chunks < 2^32, which the host checks)
+  const int row = a.chunks_magic ? (int)__umulhi((unsigned)piece, a.chunks_magic) : piece;
+  const int chunk = piece - row * a.n_chunks;
   const int gh = min(kHeads, a.g - hb * kHeads);            // live query heads of this block
-  const size_t head0 = (size_t)b * a.Hq + (size_t)kvh * a.g + (size_t)hb * kHeads;
+  const size_t head0 = (size_t)row * a.g + (size_t)hb * kHeads;   // Hq = Hkv * g
   // the chunk's share of the visual tokens (whole key groups and whole 64-token tiles) and of
-  // the 64-token text blocks
+  // the 64-token text blocks: the first `rem` chunks take one unit more than the others
   const int unit = a.unit;
-  const int n_units = a.n_vis / (a.k_group * unit);
-  const int ga = (int)((long long)n_units * chunk / a.n_chunks) * unit;
-  const int gb = (int)((long long)n_units * (chunk + 1) / a.n_chunks) * unit;
+  const int ga = chunk_first(a.units_base, a.units_rem, chunk) * unit;
+  const int gb = chunk_first(a.units_base, a.units_rem, chunk + 1) * unit;
   const int n_groups = gb - ga, nv = n_groups * a.k_group, vis0 = ga * a.k_group;
-  const int n_tblocks = (a.n_text + 63) / 64;
-  const int ba = (int)((long long)n_tblocks * chunk / a.n_chunks);
-  const int bb = (int)((long long)n_tblocks * (chunk + 1) / a.n_chunks);
+  const int ba = chunk_first(a.tblocks_base, a.tblocks_rem, chunk);
+  const int bb = chunk_first(a.tblocks_base, a.tblocks_rem, chunk + 1);
   const int txt0 = ba * 64;
   const int ntx = a.mode == kModeExtrema ? 0 : max(0, min(a.n_text, bb * 64) - txt0);
   const bool vis_wave = wave < kVisWaves;
@@ -1416,10 +1426,10 @@ void chunk_extent(const DecodeShape& s, int n_chunks, int* nv_max, int* nt_max) 
   *nv_max = 0;
   *nt_max = 0;
   for (int c = 0; c < n_chunks; ++c) {
-    const int ga = (int)((long long)n_units * c / n_chunks) * unit;
-    const int gb = (int)((long long)n_units * (c + 1) / n_chunks) * unit;
-    const int ba = (int)((long long)n_tblocks * c / n_chunks);
-    const int bb = (int)((long long)n_tblocks * (c + 1) / n_chunks);
+    const int ga = chunk_first(n_units / n_chunks, n_units % n_chunks, c) * unit;
+    const int gb = chunk_first(n_units / n_chunks, n_units % n_chunks, c + 1) * unit;
+    const int ba = chunk_first(n_tblocks / n_chunks, n_tblocks % n_chunks, c);
+    const int bb = chunk_first(n_tblocks / n_chunks, n_tblocks % n_chunks, c + 1);
     const int nv = (gb - ga) * s.k_group;
     int nt = (bb * 64 < s.n_text ? bb * 64 : s.n_text) - ba * 64;
     if (nt < 0) nt = 0;
@@ -1606,6 +1616,15 @@ hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq
   const size_t blocks = plan.nhb > 1 ? (pieces + 7) / 8 * 8 * plan.nhb : pieces;
   if (blocks > 0x7fffffffu) return hipErrorInvalidConfiguration;
   a.n_pieces = (int)pieces;
+  if (pieces * (size_t)plan.n_chunks >= ((size_t)1 << 32) || plan.nhb > 2) return hipErrorInvalidConfiguration;
+  a.chunks_magic = plan.n_chunks == 1 ? 0u : (unsigned)((((unsigned long long)1 << 32) / (unsigned)plan.n_chunks) + 1);
+  {
+    const int n_units = s.n_vis / (s.k_group * a.unit), n_tblocks = (s.n_text + 63) / 64;
+    a.units_base = n_units / plan.n_chunks;
+    a.units_rem = n_units % plan.n_chunks;
+    a.tblocks_base = n_tblocks / plan.n_chunks;
+    a.tblocks_rem = n_tblocks % plan.n_chunks;
+  }
   const dim3 grid((unsigned)blocks), block(kThreads);
   if (plan.n_chunks == 1 && plan.nhb == 1) {
     a.mode = kModeFull;
