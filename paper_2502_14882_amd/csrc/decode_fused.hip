@@ -829,10 +829,10 @@ fused_row_kernel(const FusedArgs a) {
       // accumulator layout (column = code byte, head = lane / 16).  A wave owns whole value
       // groups (v_group / 64 consecutive tiles) and folds each finished group into fp32.
       const int VG = a.v_group, tsh = VG == 128 ? 1 : 0, tpg = 1 << tsh;
-      const int n_vg = nv / VG;
+      const int n_vg = nv >> (6 + tsh);      // nv / VG, VG = 64 << tsh
       const int n_my = n_vg > wave ? ((n_vg - wave + kVisWaves - 1) / kVisWaves) << tsh : 0;
       const uint32_t* vc_row = a.v_codes + ((size_t)row * a.n_vis + vis0) * (4 * BITS);
-      const size_t g0 = (size_t)row * a.v_prow + (size_t)(vis0 / VG) * a.v_pstride;
+      const size_t g0 = (size_t)row * a.v_prow + (size_t)(vis0 >> (6 + tsh)) * a.v_pstride;
       // the lane's result columns are code byte n16: 8 (b = 1) or 2 x 4 (b = 2) consecutive channels
       const int c_lo = BITS == 1 ? 32 * (n16 >> 2) + 24 - 8 * (n16 & 3) : 16 * (n16 >> 2) + 12 - 4 * (n16 & 3);
       const int c_hi = BITS == 1 ? c_lo + 4 : c_lo + 64;

@@ -157,6 +157,7 @@ struct QArgs {
   // whole-sequence statistics only: tiles per row, and the tiles of every row that this launch
   // covers (tile_first .. tile_first + tiles_launch - 1)
   int tiles_row, tile_first, tiles_launch;
+  unsigned launch_magic;   // fl(2^32 / tiles_launch) + 1 if exact for every block of the launch, else 0
 };
 
 // Partial extrema of a row's split sp live at [(sp * 2 + {0: min, 1: max}) * kD + channel], fp16,
@@ -244,8 +245,14 @@ quantize_tile_kernel(const QArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c8 = lane & 15, ts = lane >> 4;
   // tiles never straddle rows (n_vis % 128 == 0)
-  const int wrow = kWhole ? blockIdx.x / a.tiles_launch : 0;
-  const int wtile = kWhole ? a.tile_first + blockIdx.x % a.tiles_launch : 0;
+  // block = row * tiles_launch + tile; the quotient by the host's fl(2^32 / tiles_launch) + 1 where
+  // that is exact (a division by a run-time value costs dozens of instructions ahead of the loads)
+  int wrow = 0, wtile = 0;
+  if constexpr (kWhole) {
+    wrow = a.tiles_launch == 1 ? (int)blockIdx.x
+         : a.launch_magic ? (int)__umulhi(blockIdx.x, a.launch_magic) : (int)(blockIdx.x / (unsigned)a.tiles_launch);
+    wtile = a.tile_first + (int)blockIdx.x - wrow * a.tiles_launch;
+  }
   const size_t tok0 = kWhole ? ((size_t)wrow * a.tiles_row + wtile) * kTile : (size_t)blockIdx.x * kTile;
   const v8h* src = reinterpret_cast<const v8h*>(a.x) + (tok0 + 32 * wave + ts) * (kD / 8) + c8;
 
@@ -496,12 +503,18 @@ hipError_t launch_whole(QArgs a, unsigned rows, hipStream_t stream) {
   if (e != hipSuccess) return e;
   a.tile_first = 0;
   a.tiles_launch = a.tiles_row - 1;
+  {
+    const unsigned long long blocks = (unsigned long long)rows * (unsigned)a.tiles_launch;
+    a.launch_magic = a.tiles_launch > 1 && blocks * (unsigned)a.tiles_launch < (1ull << 32)
+                         ? (unsigned)((1ull << 32) / (unsigned)a.tiles_launch + 1) : 0u;
+  }
   quantize_tile_kernel<CQ_AXIS_CHANNEL, BITS, 0>
       <<<dim3(rows * (unsigned)a.tiles_launch), dim3(kThreads), 0, stream>>>(a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   a.tile_first = a.tiles_row - 1;
   a.tiles_launch = 1;
+  a.launch_magic = 0;
   quantize_tile_kernel<CQ_AXIS_CHANNEL, BITS, 0><<<dim3(rows), dim3(kThreads), 0, stream>>>(a);
   return hipGetLastError();
 }
