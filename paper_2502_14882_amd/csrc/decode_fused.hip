@@ -210,17 +210,6 @@ __device__ inline float row_sum(float v) {
   v += dpp_f32<0x141>(v);
   return v + dpp_f32<0x140>(v);
 }
-// Sum over the wave's four rows of lanes, lane position by lane position (lane n of every row ends
-// up with v[n] + v[16 + n] + v[32 + n] + v[48 + n]): two lane swaps, no LDS.  Swapping a register
-// with its own copy hands every lane its partner's value.
-__device__ inline float rows_sum(float v) {
-  const unsigned x = __builtin_bit_cast(unsigned, v);
-  const auto h = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-  const float s = __builtin_bit_cast(float, (unsigned)h[0]) + __builtin_bit_cast(float, (unsigned)h[1]);
-  const unsigned y = __builtin_bit_cast(unsigned, s);
-  const auto q = __builtin_amdgcn_permlane16_swap(y, y, false, false);
-  return __builtin_bit_cast(float, (unsigned)q[0]) + __builtin_bit_cast(float, (unsigned)q[1]);
-}
 __device__ inline float lane_value(float v, int lane) {     // wave-uniform copy of one lane's value
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
@@ -815,6 +804,7 @@ fused_row_kernel(const FusedArgs a) {
   for (int p = 0; p < 8; ++p) acc[p] = (v4i){0, 0, 0, 0};
   float lsum[kHeads] = {0.f, 0.f, 0.f, 0.f}, msum[kHeads] = {0.f, 0.f, 0.f, 0.f};
   float tacc[kHeads][8];
+  float ttot[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // a text wave's folded sums, see below
 #pragma unroll
   for (int h = 0; h < kHeads; ++h)
 #pragma unroll
@@ -1264,11 +1254,25 @@ fused_row_kernel(const FusedArgs a) {
       const int rounds16 = ((ntx + 15) / 16 + kTextWaves - 1) / kTextWaves;
       if (11 * rounds16 < 40 * rounds64) text_values(std::integral_constant<int, 16>{});
       else text_values(std::integral_constant<int, 64>{});
-      // fold the four token slots (= the wave's four rows of lanes); every row ends up with the sum
+      // Fold the four token slots (= the wave's four rows of lanes), two values per lane swap: a
+      // swap of the upper half of head h with the lower half of head h + 2 and one add leave the
+      // half sums of both (head h in lanes 0-31, head h + 2 in lanes 32-63); the same between heads
+      // 0|2 and 1|3 over odd and even rows leaves row kb of lanes with head kb: lane (kb, n16) ends
+      // up with the wave's sums for head kb, channels 8 n16 .. + 7.  24 swaps and 24 adds for the
+      // 32 values of a lane.
+      auto bits_of = [](float v) { return __builtin_bit_cast(unsigned, v); };
+      auto float_of = [](unsigned v) { return __builtin_bit_cast(float, v); };
 #pragma unroll
-      for (int h = 0; h < kHeads; ++h)
+      for (int c = 0; c < 8; ++c) {
+        float half_sum[2];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) tacc[h][c] = rows_sum(tacc[h][c]);
+        for (int h = 0; h < 2; ++h) {
+          const auto r = __builtin_amdgcn_permlane32_swap(bits_of(tacc[h][c]), bits_of(tacc[h + 2][c]), false, false);
+          half_sum[h] = float_of(r[0]) + float_of(r[1]);
+        }
+        const auto r = __builtin_amdgcn_permlane16_swap(bits_of(half_sum[0]), bits_of(half_sum[1]), false, false);
+        ttot[c] = float_of(r[0]) + float_of(r[1]);
+      }
     }
 #pragma unroll
     for (int h = 0; h < kHeads; ++h) lsum[h] = tl[h];
@@ -1293,12 +1297,9 @@ fused_row_kernel(const FusedArgs a) {
       // channel-wise values are accumulated in units of 2^-29 (the weights' fixed point)
       partial[kb * kD + ch] = VCH ? v * 0x1p-29f : v * variant_weight<BITS>(p % kV);
     }
-  } else if (kb == 0) {
-#pragma unroll
-    for (int h = 0; h < kHeads; ++h) {
-      *reinterpret_cast<v4f*>(partial + h * kD + 8 * n16) = (v4f){tacc[h][0], tacc[h][1], tacc[h][2], tacc[h][3]};
-      *reinterpret_cast<v4f*>(partial + h * kD + 8 * n16 + 4) = (v4f){tacc[h][4], tacc[h][5], tacc[h][6], tacc[h][7]};
-    }
+  } else {      // text wave: lane (kb, n16) holds head kb, channels 8 n16 .. + 7
+    *reinterpret_cast<v4f*>(partial + kb * kD + 8 * n16) = (v4f){ttot[0], ttot[1], ttot[2], ttot[3]};
+    *reinterpret_cast<v4f*>(partial + kb * kD + 8 * n16 + 4) = (v4f){ttot[4], ttot[5], ttot[6], ttot[7]};
   }
   CQ_CLK(7);
   // the per-wave sums of the weights and of the additive value term: eight independent reductions
