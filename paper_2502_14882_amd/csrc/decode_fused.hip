@@ -140,10 +140,6 @@ __device__ inline v2i lds_read_tr8(const uint8_t* p) {
       (__attribute__((address_space(3))) v2i*)(p));
 }
 
-__device__ inline float wave_max(float v) {
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  return v;
-}
 template <int CTRL> __device__ inline float dpp_f32(float v);
 // Sum over the wave on the DPP network; the result is wave-uniform.
 __device__ inline float wave_sum(float v) {
@@ -238,10 +234,20 @@ __device__ inline float group_bias(const float (&qv0)[kHeads], const float (&qv1
   r += dpp_f32<0x4E>(g2);                  // quad_perm 2,3,0,1: lane ^ 2
   r += dpp_f32<0x124>(r);                  // row_ror 4
   r += dpp_f32<0x128>(r);                  // row_ror 8
-  r += __shfl_xor(r, 16);
-  r += __shfl_xor(r, 32);
-  const int kb = lane >> 4;
-  return __shfl(r, ((kb >> 1) & 1) | ((kb & 1) << 1));
+  // Every lane of a row now holds the row's sum for head bitrev2(lane & 3).  What is wanted is the
+  // sum over the four rows, head kb in row kb: the four heads side by side (quad broadcasts), then
+  // a transposing fold over the rows with paired lane swaps (a swap of two values and one add
+  // halve both) - all on the vector unit, where this used to take three LDS round trips per group.
+  const float h0 = dpp_f32<0x00>(r), h1 = dpp_f32<0xAA>(r);     // quad lanes 0 and 2
+  const float h2 = dpp_f32<0x55>(r), h3 = dpp_f32<0xFF>(r);     // quad lanes 1 and 3
+  auto bits_of = [](float v) { return __builtin_bit_cast(unsigned, v); };
+  auto float_of = [](unsigned v) { return __builtin_bit_cast(float, v); };
+  const auto e = __builtin_amdgcn_permlane32_swap(bits_of(h0), bits_of(h2), false, false);
+  const auto o = __builtin_amdgcn_permlane32_swap(bits_of(h1), bits_of(h3), false, false);
+  const float s02 = float_of(e[0]) + float_of(e[1]);            // head 0 in lanes 0-31, head 2 in 32-63
+  const float s13 = float_of(o[0]) + float_of(o[1]);            // head 1 | head 3
+  const auto t = __builtin_amdgcn_permlane16_swap(bits_of(s02), bits_of(s13), false, false);
+  return float_of(t[0]) + float_of(t[1]);                       // rows 0..3: heads 0, 1, 2, 3
 }
 
 // Fixed-point operands are |x| < 2^29, four signed base-256 digits.  The wide range is needed
@@ -633,10 +639,8 @@ fused_row_kernel(const FusedArgs a) {
     CQ_CLK(2);
     CQ_CLKW(32);
     // fold the 16 token lanes of every head
-    for (int o = 8; o > 0; o >>= 1) {
-      mn = fminf(mn, __shfl_xor(mn, o));
-      mx = fmaxf(mx, __shfl_xor(mx, o));
-    }
+    mn = row_min(mn);     // on the DPP network: no LDS round trips at the end of the phase
+    mx = row_max(mx);
     if (n16 == 0) {
       red[(wave * kHeads + hres) * kRedPerHead + 0] = mn;
       red[(wave * kHeads + hres) * kRedPerHead + 1] = mx;
@@ -713,8 +717,7 @@ fused_row_kernel(const FusedArgs a) {
     CQ_CLK(2);
     CQ_CLKW(32);
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      for (int o = 8; o > 0; o >>= 1) tmax[r] = fmaxf(tmax[r], __shfl_xor(tmax[r], o));
+    for (int r = 0; r < 4; ++r) tmax[r] = row_max(tmax[r]);
     if (lane == 0)
       for (int r = 0; r < 4; ++r) red[(wave * kHeads + r) * kRedPerHead + 2] = tmax[r];
   }
