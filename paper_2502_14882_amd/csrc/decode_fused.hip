@@ -695,13 +695,14 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
               for (int r = 0; r < 4; ++r) c[r] = cx[r] + dpp_f32<0x128>(cy[r]);     // row_ror 8
               const int tok = tile * 16 + 8 * u + tsub;
-              if (hsel == 0 && tok < ntx) {     // result rows 4*kb + r are heads; only heads < g exist
+              // result rows 4*kb + r are heads; only heads < gh <= 4 exist, all of them in the lanes
+              // with kb = 0: one test per lane, and the test per head is the same for the whole wave
+              if (kb == 0 && hsel == 0 && tok < ntx) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                  const int h = 4 * kb + r;
-                  if (h < gh) {
+                  if (r < gh) {
                     const float sv = c[r] * a.softmax_scale;
-                    logits[h * a.stride + nv + tok] = sv;
+                    logits[r * a.stride + nv + tok] = sv;
                     tmax[r] = fmaxf(tmax[r], sv);
                   }
                 }
@@ -1305,22 +1306,29 @@ fused_row_kernel(const FusedArgs a) {
     *reinterpret_cast<v4f*>(partial + kb * kD + 8 * n16 + 4) = (v4f){ttot[4], ttot[5], ttot[6], ttot[7]};
   }
   CQ_CLK(7);
-  // the per-wave sums of the weights and of the additive value term: eight independent reductions
-  // in one block, so they overlap (with a store between them they ran one after the other)
+  // The per-wave sums of the weights (l) and of the additive value term (m), four heads each: a
+  // transposing fold over the wave's rows of lanes with paired swaps (a swap of two values and one
+  // add halve both), then one row reduction per register: rows 0..3 of the first register end up
+  // with l[0], l[1], m[0], m[1], those of the second with l[2], l[3], m[2], m[3].
   {
-    float ls[kHeads], ms[kHeads];
+    auto bits_of = [](float v) { return __builtin_bit_cast(unsigned, v); };
+    auto float_of = [](unsigned v) { return __builtin_bit_cast(float, v); };
+    float lm[kHeads];                       // l of head h in lanes 0-31, m of head h in lanes 32-63
 #pragma unroll
     for (int h = 0; h < kHeads; ++h) {
-      ls[h] = wave_sum(lsum[h]);
-      ms[h] = wave_sum(msum[h]);
+      const auto r = __builtin_amdgcn_permlane32_swap(bits_of(lsum[h]), bits_of(msum[h]), false, false);
+      lm[h] = float_of(r[0]) + float_of(r[1]);
     }
-    if (lane == 0) {
 #pragma unroll
-      for (int h = 0; h < kHeads; ++h) {
-        red[(wave * kHeads + h) * kRedPerHead + 3] = ls[h];
-        red[(wave * kHeads + h) * kRedPerHead + 4] = ms[h];
-        if (wave == 0) red[h * kRedPerHead + 5] = mref[h];
-      }
+    for (int pair = 0; pair < 2; ++pair) {
+      const auto r = __builtin_amdgcn_permlane16_swap(bits_of(lm[2 * pair]), bits_of(lm[2 * pair + 1]), false, false);
+      const float tot = row_sum(float_of(r[0]) + float_of(r[1]));
+      if (n16 == 0)     // row kb: head 2 pair + (kb & 1), l for kb < 2 and m for kb >= 2
+        red[(wave * kHeads + 2 * pair + (kb & 1)) * kRedPerHead + 3 + (kb >> 1)] = tot;
+    }
+    if (wave == 0 && lane == 0) {
+#pragma unroll
+      for (int h = 0; h < kHeads; ++h) red[h * kRedPerHead + 5] = mref[h];
     }
   }
   CQ_CLK(8);
