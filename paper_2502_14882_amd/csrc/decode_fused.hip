@@ -388,6 +388,13 @@ fused_row_kernel(const FusedArgs a) {
   const float qmax_all = fmaxf(fmaxf(qmax[0], qmax[1]), fmaxf(qmax[2], qmax[3]));
   __syncthreads();   // red is reused below
   CQ_CLK(1);
+  // Split row: the chunk extrema of the first pass, which phase 2 needs for the calibration line,
+  // are asked for here and arrive during phase 1 (lane 16h + w: head h, chunk w; a lane beyond the
+  // live heads or chunks reads a neighbour's pair, which folds in harmlessly or is never used).
+  v2f chunk_mm = {FLT_MAX, -FLT_MAX};
+  if (a.mode == kModePartial && a.calib_mode == CQ_CALIB_DYNAMIC)
+    chunk_mm = *reinterpret_cast<const v2f*>(
+        a.ws_minmax + ((head0 + min(lane >> 4, gh - 1)) * a.n_chunks + min(lane & 15, a.n_chunks - 1)) * 2);
 
   // ring of the first value tiles of the narrow token-wise path (b <= 2): asked for during
   // phase 1, right after the first key groups, so that phase 2 does not start on a cold load
@@ -754,8 +761,10 @@ fused_row_kernel(const FusedArgs a) {
       tm_l = red[(w * kHeads + h) * kRedPerHead + 2];
     }
     if (a.mode == kModePartial && a.calib_mode == CQ_CALIB_DYNAMIC && h < gh) {
+      glo_l = chunk_mm[0];                  // chunk min(w, n_chunks - 1), asked for before phase 1
+      ghi_l = chunk_mm[1];
       const float* mm = a.ws_minmax + (head0 + h) * a.n_chunks * 2;
-      for (int cidx = w; cidx < a.n_chunks; cidx += 16) {
+      for (int cidx = w + 16; cidx < a.n_chunks; cidx += 16) {
         glo_l = fminf(glo_l, mm[2 * cidx]);
         ghi_l = fmaxf(ghi_l, mm[2 * cidx + 1]);
       }
