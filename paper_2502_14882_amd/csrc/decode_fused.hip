@@ -443,12 +443,7 @@ fused_row_kernel(const FusedArgs a) {
       };
       int wvar0, wvar1;
       const int wr0 = row_of(wc0, wvar0), wr1 = row_of(wc1, wvar1);
-      float qv0[kHeads], qv1[kHeads];
-#pragma unroll
-      for (int h = 0; h < kHeads; ++h) {
-        qv0[h] = qf[h * kD + wc0] * (a.softmax_scale * variant_weight<BITS>(wvar0));
-        qv1[h] = qf[h * kD + wc1] * (a.softmax_scale * variant_weight<BITS>(wvar1));
-      }
+      float qv0[kHeads], qv1[kHeads];               // set below, behind the first loads
       const float inv_w0 = 1.f / variant_weight<BITS>(wvar0);   // exact: powers of two
       const float inv_w1 = 1.f / variant_weight<BITS>(wvar1);
       const uint32_t* kc_lane =
@@ -617,6 +612,12 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
       for (int d = 0; d < kRK; ++d) load_group(d, wave + d * kVisWaves);
       pin_order();
+      // the lane's slice of the staged query, read while the first key groups are on their way
+#pragma unroll
+      for (int h = 0; h < kHeads; ++h) {
+        qv0[h] = qf[h * kD + wc0] * (a.softmax_scale * variant_weight<BITS>(wvar0));
+        qv1[h] = qf[h * kD + wc1] * (a.softmax_scale * variant_weight<BITS>(wvar1));
+      }
       if constexpr (kPrimeValues) {
         if (a.mode != kModeExtrema) {
 #pragma unroll
