@@ -135,6 +135,19 @@ __device__ inline T stream_load(const T* p) {
   else return *p;
 }
 
+// Streaming load through a buffer descriptor: the address is descriptor base + a per-lane offset
+// that never changes + a wave-uniform offset in a scalar register, so a load costs no vector
+// instruction for its address, and a read beyond the descriptor's size returns zeros instead of
+// needing a clamped index.
+typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
+__device__ inline __amdgpu_buffer_rsrc_t stream_buffer(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+template <bool NT>
+__device__ inline v8h buffer_load_v8h(__amdgpu_buffer_rsrc_t r, int lane_offset, int wave_offset) {
+  return __builtin_bit_cast(v8h, __builtin_amdgcn_raw_buffer_load_b128(r, lane_offset, wave_offset, NT ? 2 : 0));
+}
+
 __device__ inline v2i lds_read_tr8(const uint8_t* p) {
   return __builtin_amdgcn_ds_read_tr8_b64_v2i32(
       (__attribute__((address_space(3))) v2i*)(p));
@@ -670,17 +683,19 @@ fused_row_kernel(const FusedArgs a) {
       // the halves meet through a rotation by 8 lanes.  Twice the matrix work, which is idle
       // anyway, for half the cache-line requests.  A 16-token tile is two such 8-token halves.
       const int tsub = n16 & 7, hsel = n16 >> 3;
-      const __half* kt_row = a.k_text + ((size_t)row * a.n_text_cap + txt0) * kD + 32 * hsel + 8 * kb;
+      // the chunk's text keys as a buffer of ntx tokens: tokens past the end (a ragged last tile, a
+      // tile past the last one) read as zeros and are never stored
+      const __amdgpu_buffer_rsrc_t kt_buf =
+          stream_buffer(a.k_text + ((size_t)row * a.n_text_cap + txt0) * kD, (unsigned)ntx * kD * 2);
+      const int kt_lane = (tsub * kD + 32 * hsel + 8 * kb) * 2;
       const int n_tiles = (ntx + 15) / 16;
       v8h kt[kRingT][4];                       // [half u][line]: index 2u + line
       auto load_tile = [&](int slot, int tile) {
-        const int t0 = min(tile, n_tiles - 1) * 16 + tsub;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-          const int tok = min(t0 + 8 * u, ntx - 1);
-          const v8h* src = reinterpret_cast<const v8h*>(kt_row + (size_t)tok * kD);
-          kt[slot][2 * u] = stream_load<NT>(src);          // channels 32 hsel + 8kb .. of line 0 (channels 0..63)
-          kt[slot][2 * u + 1] = stream_load<NT>(src + 8);  // the same of line 1 (channels 64..127)
+          const int tok_bytes = (tile * 16 + 8 * u) * (kD * 2);     // wave-uniform
+          kt[slot][2 * u] = buffer_load_v8h<NT>(kt_buf, kt_lane, tok_bytes);           // channels 32 hsel + 8kb .. of line 0 (channels 0..63)
+          kt[slot][2 * u + 1] = buffer_load_v8h<NT>(kt_buf, kt_lane + 128, tok_bytes); // the same of line 1 (channels 64..127)
         }
       };
 #pragma unroll
@@ -1213,7 +1228,11 @@ fused_row_kernel(const FusedArgs a) {
     // prompt) goes out in shares of 16 so that it still occupies all text waves.
     float tl[kHeads] = {0.f, 0.f, 0.f, 0.f};
     if (ntx > 0) {
-      const __half* vt_row = a.v_text + ((size_t)row * a.n_text_cap + txt0) * kD + 8 * n16;
+      // the chunk's text values as a buffer of ntx tokens (reads past the end return zeros, which
+      // meet weights of zero)
+      const __amdgpu_buffer_rsrc_t vt_buf =
+          stream_buffer(a.v_text + ((size_t)row * a.n_text_cap + txt0) * kD, (unsigned)ntx * kD * 2);
+      const int vt_lane = (kb * kD + 8 * n16) * 2;
       auto text_values = [&](auto share_tag) {
         constexpr int SH = decltype(share_tag)::value, Q = SH / 4;
         // wave-wide loads per share, and how many of them are in flight
@@ -1223,8 +1242,7 @@ fused_row_kernel(const FusedArgs a) {
         const int p_wr = ((lane / Q) * a.stride) * 4 + (lane % Q) * 16;
         v8h ring[kDepth];
         auto load_step = [&](int slot, int sh, int s) {
-          const int tok = min(min(sh, n_sh - 1) * SH + 4 * s + kb, ntx - 1);
-          ring[slot] = stream_load<NT>(reinterpret_cast<const v8h*>(vt_row + (size_t)tok * kD));
+          ring[slot] = buffer_load_v8h<NT>(vt_buf, vt_lane, (sh * SH + 4 * s) * (kD * 2));
         };
 #pragma unroll
         for (int s = 0; s < kDepth; ++s) load_step(s, tw, s);
