@@ -1,7 +1,7 @@
 /*
  * cq.h - C ABI of the CalibQuant hot path on MI355X (gfx950).
  *
- * Two operations of arxiv 2502.14882:
+ * The two operations of the hot path of arxiv 2502.14882:
  *   cq_quantize_kv   uniform b-bit quantization of the visual-token KV cache
  *                    (Sec. 2.2 quantize equation; Sec. 3.1 channel-wise statistics;
  *                    packing appendix), producing packed codes + scale + min;
@@ -9,7 +9,11 @@
  *                    directly (Sec. 3.1 post-scaling, Sec. 3.2 calibration g,
  *                    Sec. 2.1 softmax(.)V), with the 16-bit text-token tail of
  *                    Sec. 3 / Sec. 3.3 ("irregular matrix shape") merged into the
- *                    same softmax.
+ *                    same softmax;
+ * and the steps either side of them:
+ *   cq_append_text_kv  growth of the 16-bit tail between decode steps;
+ *   cq_tau_search      the grid search of the calibration parameters (Sec. 3.2);
+ * plus measurement aids for the benchmark (cq_bench_*) and a kernel-path switch for tests.
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
