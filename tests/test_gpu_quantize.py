@@ -243,3 +243,18 @@ def test_random_layouts_on_the_tuned_quantizer(kernel_path):
                  what="trial %d b=%d kg=%d vg=%d axes=%d%d" % (trial, bits, kg, vg, ka, va))
     finally:
         cq.cq_set_kernel_path(prev)
+
+
+@pytest.mark.tuned_only
+def test_traffic_measurement_aid_runs(kernel_path):
+    """The quantizer's traffic skeleton (measurement aid) reads its tiles and writes the byte counts
+    it is asked for, and nothing beyond them."""
+    n_tiles, cb, mb = 37, 2048, 768
+    x = torch.randn(n_tiles * 128, 128, device="cuda").half()
+    codes = torch.full((n_tiles * cb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    meta = torch.full((n_tiles * mb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    cq.cq_bench_tile_traffic(x, codes, meta, n_tiles, cb, mb)
+    torch.cuda.synchronize()
+    assert bool((codes[n_tiles * cb:] == 0xA5).all()) and bool((meta[n_tiles * mb:] == 0xA5).all())
+    # every tile wrote something (the fold of a random tile is not the fill pattern throughout)
+    assert not bool((codes[:n_tiles * cb].view(n_tiles, cb) == 0xA5).all(dim=1).any())
