@@ -57,8 +57,9 @@ constexpr int kRedPerHead = 6;
 // loads in flight per wave, in units of one key group / value tile / text tile / 4 text tokens.
 // Deeper is not better on this chip: with much more in flight per CU the achieved bandwidth drops
 // (also seen on a plain streaming read).  Measured: on long whole rows (64 key groups) 3 key
-// groups in flight are 1-2 % faster than 2 and 4 are 8 % slower, on short or split rows 3 are 3-5 %
-// slower (the kernel's RK parameter); the other rings make no difference.
+// groups in flight are 1-2 % faster than 2 and 4 are 8 % slower (about 1 % faster with groups of
+// 32 tokens, slower with 64), on short or split rows 3 are 3-5 % slower (the kernel's RK
+// parameter); the other rings make no difference.
 #ifndef CQ_RING_K
 #define CQ_RING_K 2
 #endif
@@ -1631,6 +1632,11 @@ hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq
     if (s.bits == 1) { kern = fused_row_kernel<8, 1, false, false, true, 3>; slot = 26; }
     else { kern = fused_row_kernel<8, 2, false, false, true, 3>; slot = 27; }
   }
+  if (plan.n_chunks == 1 && plan.nhb == 1 && !k_whole && !vch && s.k_group == 32 && s.bits <= 2 &&
+      s.n_vis >= 48 * 128) {
+    if (s.bits == 1) { kern = fused_row_kernel<2, 1, false, false, true, 3>; slot = 28; }
+    else { kern = fused_row_kernel<2, 2, false, false, true, 3>; slot = 29; }
+  }
   // two head blocks per KV head: the twin workgroups share their lines through L2 (ordinary loads)
   if (plan.nhb > 1 && !k_whole && !vch && s.k_group == 128 && s.bits <= 2) {
     if (s.bits == 1) { kern = fused_row_kernel<8, 1, false, false, false>; slot = 24; }
@@ -1638,7 +1644,7 @@ hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq
   }
   // the kernel's dynamic LDS limit is raised once per (device, kernel) and only ever grows;
   // concurrent callers may both raise it, which is harmless
-  static std::atomic<size_t> configured[kMaxDevices][28];
+  static std::atomic<size_t> configured[kMaxDevices][30];
   int dev = 0;
   hipError_t de = hipGetDevice(&dev);
   if (de != hipSuccess) return de;

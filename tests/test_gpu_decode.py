@@ -189,7 +189,7 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path):
 # the layouts that bench.py times on configs[2]: (bits, key group, value axis, value group); a group
 # of 0 stands for the whole sequence
 FULL_SIZE_LAYOUTS = [(1, 128, 1, 128), (2, 128, 1, 128), (4, 128, 1, 128), (8, 128, 1, 128),
-                     (1, 32, 1, 128), (1, 64, 1, 128), (1, 128, 0, 128), (2, 128, 0, 128),
+                     (1, 32, 1, 128), (2, 32, 1, 128), (1, 64, 1, 128), (1, 128, 0, 128), (2, 128, 0, 128),
                      (1, 0, 1, 128), (1, 0, 0, 0), (2, 0, 0, 0)]
 
 
