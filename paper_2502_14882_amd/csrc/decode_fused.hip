@@ -20,8 +20,9 @@
 // The additive term of post-scaling (q . min_t, resp. sum_j p_j min_j) stays in fp32.
 //
 // Work split inside the workgroup (12 waves): waves 0..7 stream the packed visual cache, waves
-// 8..11 stream the fp16 text tail at the same time, so the bandwidth-heavy text reads overlap the
-// compute-heavy visual phases.  Every stream keeps a ring of loads several tiles deep in flight.
+// 8..11 stream the fp16 text tail at the same time (its two contractions on the fp16 matrix cores:
+// 16 x 16 x 32 for the logits, 4 x 4 x 4 blocks for the values), so the bandwidth-heavy text reads
+// overlap the compute-heavy visual phases.  Every stream keeps a ring of loads several tiles deep in flight.
 // Two rules keep those rings in flight (the compiler's wait counting is exact only in straight
 // code): the steady-state loops have no branch around a global load (clamped addresses, tails
 // apart, group ends known at compile time), and nothing keeps a loaded register alive past the
@@ -45,6 +46,7 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 
 constexpr int kD = 128;             // head_dim
 constexpr int kVisWaves = 8;        // waves on the packed visual cache
@@ -833,12 +835,7 @@ fused_row_kernel(const FusedArgs a) {
 #pragma unroll
   for (int p = 0; p < 8; ++p) acc[p] = (v4i){0, 0, 0, 0};
   float lsum[kHeads] = {0.f, 0.f, 0.f, 0.f}, msum[kHeads] = {0.f, 0.f, 0.f, 0.f};
-  float tacc[kHeads][8];
-  float ttot[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // a text wave's folded sums, see below
-#pragma unroll
-  for (int h = 0; h < kHeads; ++h)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) tacc[h][i] = 0.f;
+  float ttot[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // a text wave's sums, see below
 
   if (vis_wave) {
     if constexpr (VCH) { if (nv > 0) {
@@ -1222,9 +1219,16 @@ fused_row_kernel(const FusedArgs a) {
     CQ_CLKW(48);
   } else {
     // text tail.  lane = (token slot kb, channels 8 * n16 .. +7): one 16-byte load covers 8 channels
-    // of one token, a wave-wide load covers 4 tokens.  The tail is handed to the text waves in
-    // shares of SH tokens; the weights of a share are computed once (lane = token) and staged in
-    // the share's own logit slots (SH / 4 slots of 16 bytes in each of the four head rows).
+    // of one token, a wave-wide load covers 4 tokens.  The contraction over tokens runs on the
+    // matrix cores as 16 independent 4 x 4 x 4 products per instruction (heads x channels x
+    // tokens; fp16 operands, fp32 sums): a 4 x 4 transpose over the wave's four rows of lanes
+    // (two lane swaps each way) and four byte permutes leave every lane with the four tokens of
+    // its two channels 8 n16 + 2 kb, + 1, and the weights come as fp16 pairs hi + lo / 2^11 of
+    // 2^10 p (p <= 1; products of fp16 numbers are exact in fp32), so the sum carries the weights
+    // to 2^-22 as the fp32 multiply-adds it replaces did to 2^-24.  The tail is handed to the text
+    // waves in shares of SH tokens; the weights of a share are computed once (lane = token) and
+    // staged in the share's own logit slots (SH * 4 bytes in each of the four head rows), one
+    // 64-byte record per load step: [hi | lo][head][token of the step].
     // Shares of 64 tokens are the efficient ones; a short tail (a split row's chunk, a small
     // prompt) goes out in shares of 16 so that it still occupies all text waves.
     float tl[kHeads] = {0.f, 0.f, 0.f, 0.f};
@@ -1234,13 +1238,17 @@ fused_row_kernel(const FusedArgs a) {
       const __amdgpu_buffer_rsrc_t vt_buf =
           stream_buffer(a.v_text + ((size_t)row * a.n_text_cap + txt0) * kD, (unsigned)ntx * kD * 2);
       const int vt_lane = (kb * kD + 8 * n16) * 2;
+      v4f acc_hi[2], acc_lo[2];              // [channel 8 n16 + 2 kb + i][head]
+#pragma unroll
+      for (int i = 0; i < 2; ++i) acc_hi[i] = acc_lo[i] = (v4f){0.f, 0.f, 0.f, 0.f};
       auto text_values = [&](auto share_tag) {
-        constexpr int SH = decltype(share_tag)::value, Q = SH / 4;
-        // wave-wide loads per share, and how many of them are in flight
-        constexpr int kSteps = SH / 4, kDepth = kRingTV < kSteps ? kRingTV : kSteps;
+        constexpr int SH = decltype(share_tag)::value;
+        // wave-wide loads per share, how many of them are in flight, records per head row
+        constexpr int kSteps = SH / 4, kDepth = kRingTV < kSteps ? kRingTV : kSteps, kRecs = SH / 16;
         static_assert(kSteps % kDepth == 0, "the ring divides a share");
         const int n_sh = (ntx + SH - 1) / SH;
-        const int p_wr = ((lane / Q) * a.stride) * 4 + (lane % Q) * 16;
+        const int rec_wr = (((lane >> 2) / kRecs) * a.stride) * 4 + ((lane >> 2) % kRecs) * 64 + (lane & 3) * 2;
+        const int rec_rd = (lane & 3) * 8;          // matrix row = lane % 4 = head
         v8h ring[kDepth];
         auto load_step = [&](int slot, int sh, int s) {
           ring[slot] = buffer_load_v8h<NT>(vt_buf, vt_lane, (sh * SH + 4 * s) * (kD * 2));
@@ -1263,18 +1271,40 @@ fused_row_kernel(const FusedArgs a) {
           for (int h = 0; h < kHeads; ++h) tl[h] += pv[h];
           uint8_t* pb = lbytes + (size_t)(nv + t0) * 4;
           __builtin_amdgcn_wave_barrier();
-          if (lane < SH) *reinterpret_cast<v4f*>(pb + p_wr) = pv;          // zero beyond nt
+          asm volatile("" ::: "memory");     // the records overwrite logits read just above
+          if (lane < SH) {                                                  // zero beyond nt
+#pragma unroll
+            for (int h = 0; h < kHeads; ++h) {
+              const float ps = pv[h] * 1024.f;
+              const _Float16 hi = (_Float16)ps;
+              const _Float16 lo = (_Float16)((ps - (float)hi) * 2048.f);
+              *reinterpret_cast<_Float16*>(pb + rec_wr + 8 * h) = hi;
+              *reinterpret_cast<_Float16*>(pb + rec_wr + 32 + 8 * h) = lo;
+            }
+          }
           lds_publish();
 #pragma unroll
           for (int s = 0; s < kSteps; ++s) {
             const int slot = s % kDepth;
-            const int l = 4 * s + kb;                       // token slot inside the share
-            const v4f pp = *reinterpret_cast<const v4f*>(pb + ((l / Q) * a.stride) * 4 + (l % Q) * 16);
-            const v8h raw = ring[slot];
-#pragma unroll
-            for (int h = 0; h < kHeads; ++h)
-#pragma unroll
-              for (int c = 0; c < 8; ++c) tacc[h][c] = fmaf(pp[h], (float)raw[c], tacc[h][c]);
+            const uint8_t* rec = pb + ((s / kRecs) * a.stride) * 4 + (s % kRecs) * 64 + rec_rd;
+            const v4h p_hi = *reinterpret_cast<const v4h*>(rec);
+            const v4h p_lo = *reinterpret_cast<const v4h*>(rec + 32);
+            const v4u32 raw = __builtin_bit_cast(v4u32, ring[slot]);
+            // word j of token kb -> row j of lanes holds word j of tokens 0..3
+            const v2u lo2 = __builtin_amdgcn_permlane32_swap(raw[0], raw[2], false, false);
+            const v2u hi2 = __builtin_amdgcn_permlane32_swap(raw[1], raw[3], false, false);
+            const v2u t01 = __builtin_amdgcn_permlane16_swap(lo2[0], hi2[0], false, false);
+            const v2u t23 = __builtin_amdgcn_permlane16_swap(lo2[1], hi2[1], false, false);
+            // the even channel's four tokens from the low halves, the odd channel's from the high
+            const v2u even = {__builtin_amdgcn_perm(t01[1], t01[0], 0x05040100u),
+                              __builtin_amdgcn_perm(t23[1], t23[0], 0x05040100u)};
+            const v2u odd = {__builtin_amdgcn_perm(t01[1], t01[0], 0x07060302u),
+                             __builtin_amdgcn_perm(t23[1], t23[0], 0x07060302u)};
+            const v4h v_even = __builtin_bit_cast(v4h, even), v_odd = __builtin_bit_cast(v4h, odd);
+            acc_hi[0] = __builtin_amdgcn_mfma_f32_4x4x4f16(p_hi, v_even, acc_hi[0], 0, 0, 0);
+            acc_hi[1] = __builtin_amdgcn_mfma_f32_4x4x4f16(p_hi, v_odd, acc_hi[1], 0, 0, 0);
+            acc_lo[0] = __builtin_amdgcn_mfma_f32_4x4x4f16(p_lo, v_even, acc_lo[0], 0, 0, 0);
+            acc_lo[1] = __builtin_amdgcn_mfma_f32_4x4x4f16(p_lo, v_odd, acc_lo[1], 0, 0, 0);
             // refill: step s + kDepth of this share, or the start of the wave's next share
             if (s + kDepth < kSteps) load_step(slot, sh, s + kDepth);
             else load_step(slot, sh + kTextWaves, s + kDepth - kSteps);
@@ -1287,25 +1317,12 @@ fused_row_kernel(const FusedArgs a) {
       const int rounds16 = ((ntx + 15) / 16 + kTextWaves - 1) / kTextWaves;
       if (11 * rounds16 < 40 * rounds64) text_values(std::integral_constant<int, 16>{});
       else text_values(std::integral_constant<int, 64>{});
-      // Fold the four token slots (= the wave's four rows of lanes), two values per lane swap: a
-      // swap of the upper half of head h with the lower half of head h + 2 and one add leave the
-      // half sums of both (head h in lanes 0-31, head h + 2 in lanes 32-63); the same between heads
-      // 0|2 and 1|3 over odd and even rows leaves row kb of lanes with head kb: lane (kb, n16) ends
-      // up with the wave's sums for head kb, channels 8 n16 .. + 7.  24 swaps and 24 adds for the
-      // 32 values of a lane.
-      auto bits_of = [](float v) { return __builtin_bit_cast(unsigned, v); };
-      auto float_of = [](unsigned v) { return __builtin_bit_cast(float, v); };
+      // lane (kb, n16): the wave's sums for heads 0..3, channels 8 n16 + 2 kb and + 1
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        float half_sum[2];
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          const auto r = __builtin_amdgcn_permlane32_swap(bits_of(tacc[h][c]), bits_of(tacc[h + 2][c]), false, false);
-          half_sum[h] = float_of(r[0]) + float_of(r[1]);
-        }
-        const auto r = __builtin_amdgcn_permlane16_swap(bits_of(half_sum[0]), bits_of(half_sum[1]), false, false);
-        ttot[c] = float_of(r[0]) + float_of(r[1]);
-      }
+        for (int h = 0; h < kHeads; ++h)
+          ttot[2 * h + i] = fmaf(acc_lo[i][h], 0x1p-11f, acc_hi[i][h]) * 0x1p-10f;
     }
 #pragma unroll
     for (int h = 0; h < kHeads; ++h) lsum[h] = tl[h];
@@ -1330,9 +1347,10 @@ fused_row_kernel(const FusedArgs a) {
       // channel-wise values are accumulated in units of 2^-29 (the weights' fixed point)
       partial[kb * kD + ch] = VCH ? v * 0x1p-29f : v * variant_weight<BITS>(p % kV);
     }
-  } else {      // text wave: lane (kb, n16) holds head kb, channels 8 n16 .. + 7
-    *reinterpret_cast<v4f*>(partial + kb * kD + 8 * n16) = (v4f){ttot[0], ttot[1], ttot[2], ttot[3]};
-    *reinterpret_cast<v4f*>(partial + kb * kD + 8 * n16 + 4) = (v4f){ttot[4], ttot[5], ttot[6], ttot[7]};
+  } else {      // text wave: lane (kb, n16) holds heads 0..3, channels 8 n16 + 2 kb and + 1
+#pragma unroll
+    for (int h = 0; h < kHeads; ++h)
+      *reinterpret_cast<v2f*>(partial + h * kD + 8 * n16 + 2 * kb) = (v2f){ttot[2 * h], ttot[2 * h + 1]};
   }
   CQ_CLK(7);
   // The per-wave sums of the weights (l) and of the additive value term (m), four heads each: a
