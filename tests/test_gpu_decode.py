@@ -486,15 +486,16 @@ def test_tuned_wide_codes_on_split_and_full_length_rows(kernel_path, bits, monke
 def test_text_only_rows_on_the_tuned_kernel(kernel_path, n_text, n_q_heads):
     """A cache left entirely in fp16 (the 16-bit baseline of the benchmark): the text waves alone,
     with shares of 64 and of 16 tokens, ragged ends and a padded head.  The weights reach the value
-    contraction as fp16 pairs; 6e-4 holds only while they keep their full precision (one fp16
-    number per weight gives ~5e-4 on top of the output's rounding)."""
+    contraction as fp16 pairs hi + lo: the error stays the fp16 rounding of the output (2.0e-4 to
+    2.2e-4 measured), where one fp16 number per weight would add 2^-11 / sqrt(3) = 2.8e-4 in
+    quadrature (3.5e-4), hence the bar of 3e-4 here."""
     w = synth.WORKLOADS[2].replace(batch=2, n_kv_heads=1, n_q_heads=n_q_heads, n_vis=0,
                                    n_text=n_text, seed=7300 + n_text)
     c = Case(w, H.layout_of(w))
     prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
-        c.check(cq.CQ_CALIB_NONE, tol=6e-4)
-        c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, tol=6e-4)      # no visual tokens: nothing to calibrate
+        c.check(cq.CQ_CALIB_NONE, tol=3e-4)
+        c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, tol=3e-4)      # no visual tokens: nothing to calibrate
     finally:
         cq.cq_set_kernel_path(prev)
 
