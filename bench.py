@@ -42,8 +42,8 @@ def algorithmic_bytes(w, bits, k_group, v_group):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="index into the workload list")
     ap.add_argument("--bits", type=int, default=1)
     ap.add_argument("--group", type=int, default=128,
@@ -80,7 +80,7 @@ def main() -> int:
     cq.lib()    # fail loudly if libcq.so is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    cq.cq_set_kernel_path({"auto": cq.CQ_PATH_AUTO, "generic": cq.CQ_PATH_GENERIC,
+    cq.cq_bench_set_kernel_path({"auto": cq.CQ_PATH_AUTO, "generic": cq.CQ_PATH_GENERIC,
                            "tuned": cq.CQ_PATH_TUNED}[args.path])
 
     w = synth.WORKLOADS[args.config]
@@ -190,7 +190,7 @@ def main() -> int:
         if i == 0:
             sample0 = {n: x[n][:1].cpu() for n in ("k", "v", "q", "k_text", "v_text")}
         del x
-    ws = torch.empty(cq.cq_decode_workspace_bytes(lay, w.n_text), dtype=torch.uint8, device=dev)
+    ws = torch.empty(cq.cq_decode_workspace_bytes(lay, w.n_text, calib), dtype=torch.uint8, device=dev)
 
     def step(i):
         s = sets[i % n_sets]
@@ -217,22 +217,37 @@ def main() -> int:
     eager_mean_ms = sum(dev_ms) / len(dev_ms)
 
     if args.launch == "graph":
-        # the timed region: exactly `steps` steps, recorded once into a HIP graph (the library
-        # allocates nothing and calls no blocking API per step) and replayed
+        # The timed region.  A step is one cq_decode_attn call; `steps` of them are recorded once
+        # into a HIP graph (the library allocates nothing and calls no blocking API per step) and
+        # the graph is replayed back to back until at least MIN_TIMED launches lie between the two
+        # events, whatever `steps` is: a replay costs ~0.3 ms before its first kernel, which a short
+        # region would book on its few steps.  At least MIN_SETTLE launches run untimed immediately
+        # before the first event, without a synchronisation in between, so that the timed replays
+        # are already queued behind work in flight and the clocks have settled.
+        MIN_TIMED, MIN_SETTLE = 1000, 200
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             for i in range(args.steps):
                 step(i)
+        n_timed = -(-MIN_TIMED // args.steps)
+        n_settle = -(-MIN_SETTLE // args.steps)
         graph.replay()                      # untimed: instantiation and upload
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
+        for _ in range(n_settle):
+            graph.replay()
         e0.record()
-        graph.replay()
+        for _ in range(n_timed):
+            graph.replay()
         e1.record()
         torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        mean_ms = e0.elapsed_time(e1) / args.steps
+        wall_all_ms = (time.perf_counter() - t0) * 1e3
+        timed_launches = n_timed * args.steps
+        mean_ms = e0.elapsed_time(e1) / timed_launches
+        # host wall clock over settle + timed replays, per launch: an upper bound that also holds
+        # the launch of the first replay
+        wall_ms = wall_all_ms / ((n_settle + n_timed) * args.steps)
         # a replayed step must give what the eager step gives
         last = sets[(args.steps - 1) % n_sets]
         from_graph = last["out"].clone()
@@ -242,9 +257,12 @@ def main() -> int:
             raise RuntimeError("graph replay and eager launch disagree")
     else:
         wall_ms, mean_ms = eager_wall_ms, eager_mean_ms
+        timed_launches = n_ev
 
     kv_tokens = w.batch * (w.n_vis + w.n_text)
-    value = kv_tokens / (wall_ms * 1e-3)
+    # throughput and ms_per_step from the device time of the timed region (HIP events on the
+    # launches' stream); the host's wall clock per launch is reported next to it
+    value = kv_tokens / (mean_ms * 1e-3)
     achieved = bytes_call / (mean_ms * 1e-3) / 1e9
 
     # practical ceiling: a plain streaming read of the same number of bytes, cold each time
@@ -284,13 +302,13 @@ def main() -> int:
             cq.cq_decode_attn(lay16, sets[0]["q"], None, None, k16, v16, n_all, none, 0.0,
                               sets[0]["out"], ws16)
 
-        prev_path = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+        prev_path = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
         try:
             step16(0)
             torch.cuda.synchronize()
             kernel16 = "fused_row_kernel, text path only (one launch)"
         except cq.CqError:
-            cq.cq_set_kernel_path(cq.CQ_PATH_AUTO)
+            cq.cq_bench_set_kernel_path(cq.CQ_PATH_AUTO)
             kernel16 = "shape-agnostic kernels (the row does not fit the tuned kernel's LDS)"
         n16 = 20 if kernel16.startswith("fused") else 3
         for i in range(2):
@@ -302,7 +320,7 @@ def main() -> int:
             step16(i)
         e1.record()
         torch.cuda.synchronize()
-        cq.cq_set_kernel_path(prev_path)
+        cq.cq_bench_set_kernel_path(prev_path)
         ms16 = e0.elapsed_time(e1) / n16
         bytes16 = w.batch * w.n_kv_heads * n_all * per_text + 2 * w.batch * w.n_q_heads * w.head_dim * 2
         fp16_baseline = {"ms": ms16, "kernel": kernel16, "bytes_per_call": bytes16,
@@ -349,27 +367,40 @@ def main() -> int:
     q_ms = sorted(quant_ms)[len(quant_ms) // 2]
 
     # which kernel ran: forcing the tuned path fails loudly when the layout would fall back
-    prev_path = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev_path = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         step(0)
         torch.cuda.synchronize()
         fused = args.path != "generic"
     except cq.CqError:
         fused = False
-    cq.cq_set_kernel_path(prev_path)
+    cq.cq_bench_set_kernel_path(prev_path)
     kernel_name = ("fused_row_kernel<%d> (the call's only launch)" % (min(k_group, 128) // 16) if fused
                    else "scores_kernel + pv_kernel + combine_kernel (all launches of one call)")
-    traffic = None
+    # HBM bytes per launch from hardware counters: NOT measured by this run.  The committed summary
+    # of two rocprofv3 --pmc runs of this command holds the figure together with the SHA-256 of the
+    # kernel source it was taken on; it is reported only while that source is unchanged.
+    traffic, traffic_source = None, None
     if (fused and args.config == 2 and args.bits == 1 and args.group == 128 and not args.batch and not args.n_vis and args.n_text < 0
             and args.v_axis == "token"):
-        # counter-derived HBM bytes per launch from the committed rocprofv3 summary of this command
+        import hashlib
+        prof = os.path.join("profiles", "fused_row_kernel_configs2_hbm_traffic.txt")
+        src = os.path.join("paper_2502_14882_amd", "csrc", "decode_fused.hip")
         try:
-            for line in open(os.path.join(ROOT, "profiles",
-                                          "fused_row_kernel_configs2_hbm_traffic.txt")):
+            sha_now = hashlib.sha256(open(os.path.join(ROOT, src), "rb").read()).hexdigest()[:16]
+            val, sha_prof = None, None
+            for line in open(os.path.join(ROOT, prof)):
                 if line.startswith("fused_row_kernel_configs2_traffic_bytes_per_launch:"):
-                    traffic = float(line.split(":")[1])
+                    val = float(line.split(":")[1])
+                if line.startswith("kernel_source_sha256_16:"):
+                    sha_prof = line.split(":")[1].strip()
+            if val is not None and sha_prof == sha_now:
+                traffic = val
+                traffic_source = "%s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, taken on %s sha256 %s)" % (prof, src, sha_prof)
+            else:
+                traffic_source = "not reported: %s was taken on another version of %s" % (prof, src)
         except OSError:
-            traffic = None
+            traffic_source = "not reported: no committed counter summary"
 
     result = {
         "metric": "decode_attention_kv_tokens_per_s",
@@ -378,7 +409,7 @@ def main() -> int:
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": wall_ms,
+        "ms_per_step": mean_ms,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -392,10 +423,16 @@ def main() -> int:
                    "calib": "dynamic tau=(1,2)",
                    "kernel_path": args.path, "input_sets": n_sets},
         "launch": args.launch,
+        "timed_region": {"launches_between_events": timed_launches,
+                         "note": "the graph of `steps` launches replayed back to back, preceded by "
+                                 ">= 200 untimed launches with no synchronisation in between"
+                                 if args.launch == "graph" else "one call per step from Python",
+                         "host_wall_ms_per_launch": wall_ms},
         "device_ms": {"mean_in_timed_region": mean_ms, "eager_median": med_ms, "eager_min": min_ms,
                       "eager_mean": eager_mean_ms, "eager_wall_per_step": eager_wall_ms},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": traffic_source,
                      "kernel": kernel_name,
                      "algorithmic_bytes_per_call": bytes_call,
                      "stream_read_same_bytes": {"ms": stream_ms,

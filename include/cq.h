@@ -12,8 +12,8 @@
  *                    same softmax;
  * and the steps either side of them:
  *   cq_append_text_kv  growth of the 16-bit tail between decode steps;
- *   cq_tau_search      the grid search of the calibration parameters (Sec. 3.2);
- * plus measurement aids for the benchmark (cq_bench_*) and a kernel-path switch for tests.
+ *   cq_tau_search      the grid search of the calibration parameters (Sec. 3.2).
+ * (Measurement aids and the test switches live in cq_bench.h, not here.)
  *
  * Conventions
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
@@ -25,6 +25,8 @@
  *   - Return value: CQ_OK (0) or a negative cq_status.  Argument errors are found on
  *     the host before any HIP call, so nothing is launched when one is returned.
  *     cq_last_error() gives a message for the last failure on the calling thread.
+ *   - The library keeps no state between calls beyond that thread-local message (and caches
+ *     of device properties); it reads no environment variable.
  *   - Inputs must be finite; NaN/Inf behaviour is undefined (the paper is silent).
  *   - Query head hq attends to KV head hq / (n_q_heads / n_kv_heads).
  */
@@ -117,9 +119,16 @@ typedef struct {
   float gamma, delta; /* CQ_CALIB_FIXED only; delta > gamma */
 } cq_calib_t;
 
-/* Bytes of scratch cq_decode_attn needs for this shape (a multiple of 256, > 0).
- * Returns 0 if the layout is invalid. */
-size_t cq_decode_workspace_bytes(const cq_layout_t *layout, int32_t n_text);
+/* Bytes of scratch cq_decode_attn needs for this shape and calibration (a multiple of 256,
+ * > 0): what the kernels that the call will select use.  A row that one workgroup can own
+ * (the tuned one-launch kernel) needs the minimum of 256 bytes; a row split over several
+ * workgroups needs one (m, l, acc[d]) partial of the online softmax per (batch, query head,
+ * chunk), plus the chunks' logit extrema with CQ_CALIB_DYNAMIC; the shape-agnostic kernels
+ * also keep one float per (batch, query head, token).  n_text is the largest tail length the
+ * workspace has to serve; `calib` may be NULL (= CQ_CALIB_NONE).  Returns 0 if the layout,
+ * n_text or the calibration mode is invalid. */
+size_t cq_decode_workspace_bytes(const cq_layout_t *layout, int32_t n_text,
+                                 const cq_calib_t *calib);
 
 /*
  * One decode step: out = softmax([g(s_vis), s_txt]) [V_deq; V_text]   (Sec. 2.1, 3.2)
@@ -134,10 +143,12 @@ size_t cq_decode_workspace_bytes(const cq_layout_t *layout, int32_t n_text);
  *   calib        in : may be NULL (= CQ_CALIB_NONE)
  *   softmax_scale   : 0 means 1/sqrt(d)
  *   out_f16      out: fp16 [B, Hq, d]
- *   workspace       : device scratch of at least cq_decode_workspace_bytes(), 256-byte
- *                     aligned; contents undefined before and after; two calls that
- *                     overlap in time must not share it
+ *   workspace       : device scratch of at least cq_decode_workspace_bytes(layout, n_text,
+ *                     calib), 256-byte aligned; contents undefined before and after; two
+ *                     calls that overlap in time must not share it
  * n_vis + n_text must be >= 1.
+ * Errors: CQ_ERR_NULL, CQ_ERR_ALIGN, CQ_ERR_SHAPE, CQ_ERR_UNSUPPORTED (calibration mode),
+ * CQ_ERR_WORKSPACE (NULL, misaligned or too small), CQ_ERR_HIP.
  */
 int cq_decode_attn(const cq_layout_t *layout, const void *q_f16, const cq_qtensor_t *k,
                    const cq_qtensor_t *v, const void *k_text_f16, const void *v_text_f16,
@@ -155,6 +166,32 @@ int cq_decode_attn(const cq_layout_t *layout, const void *q_f16, const cq_qtenso
 int cq_append_text_kv(const cq_layout_t *layout, void *k_text_f16, void *v_text_f16,
                       int32_t n_text, int32_t n_text_cap, const void *k_new_f16,
                       const void *v_new_f16, void *stream);
+
+/*
+ * The same two steps with the tail length held in DEVICE memory, so that one decode step
+ * (append the new token, then attend) can be recorded once into a HIP graph and replayed while
+ * the tail grows (Sec. 2.1: every decode step appends the new key and value to the cache).
+ *   n_text_dev   : device int32, the current number of text tokens of every sequence.
+ *   n_text_max   : HOST upper bound of *n_text_dev for the lifetime of the recording,
+ *                  0 <= n_text_max <= n_text_cap.  It sizes the launches, the workspace
+ *                  (cq_decode_workspace_bytes(layout, n_text_max, calib)) and the on-chip
+ *                  buffers; the kernels read min(max(*n_text_dev, 0), n_text_max) tokens.
+ * cq_append_text_kv_devlen writes the new token to slot *n_text_dev of each tail and then
+ * increments *n_text_dev; a full tail (*n_text_dev >= n_text_cap) or a negative length leaves
+ * the tails and the counter unchanged.  cq_decode_attn_devlen is cq_decode_attn otherwise;
+ * n_vis + *n_text_dev must be >= 1 when its kernels run (not checkable on the host).
+ * Same errors as the host-length calls, plus CQ_ERR_NULL for n_text_dev and CQ_ERR_ALIGN when
+ * it is not 4-byte aligned.  Asynchronous on `stream`; nothing is allocated and nothing is
+ * read back to the host.
+ */
+int cq_append_text_kv_devlen(const cq_layout_t *layout, void *k_text_f16, void *v_text_f16,
+                             int32_t *n_text_dev, int32_t n_text_cap, const void *k_new_f16,
+                             const void *v_new_f16, void *stream);
+int cq_decode_attn_devlen(const cq_layout_t *layout, const void *q_f16, const cq_qtensor_t *k,
+                          const cq_qtensor_t *v, const void *k_text_f16, const void *v_text_f16,
+                          const int32_t *n_text_dev, int32_t n_text_max, int32_t n_text_cap,
+                          const cq_calib_t *calib, float softmax_scale, void *out_f16,
+                          void *workspace, size_t workspace_bytes, void *stream);
 
 /* Grid search of the calibration parameters (Sec. 3.2: tau1, tau2 are searched on a grid once and
  * then fixed).  For every pair (tau1[i], tau2[j]) computes the mean squared difference between
@@ -185,31 +222,6 @@ int cq_tau_search(const cq_layout_t *layout, const void *q_f16, const void *k_ex
                   int32_t n_text_cap, const float *tau1, int32_t n_tau1, const float *tau2,
                   int32_t n_tau2, float softmax_scale, double *mse_out, void *workspace,
                   size_t workspace_bytes, void *stream);
-
-/* Kernel selection, for tests and comparisons.  AUTO picks the tuned kernels when the
- * shape allows and the generic ones otherwise; GENERIC forces the shape-agnostic
- * kernels; TUNED returns CQ_ERR_UNSUPPORTED instead of falling back.  Process-wide.
- * Returns the previous value, or CQ_ERR_UNSUPPORTED for an unknown one. */
-enum { CQ_PATH_AUTO = 0, CQ_PATH_GENERIC = 1, CQ_PATH_TUNED = 2 };
-int cq_set_kernel_path(int path);
-
-/* Measurement aid, not part of the method: enqueue a plain streaming read of `bytes` bytes at
- * `buf` (device, 16-byte aligned).  `sink` is a device float that is practically never written
- * (may be NULL).  The benchmark times it to report the practical read ceiling of the box next to
- * the published HBM peak. */
-int cq_bench_stream_read(const void *buf, size_t bytes, void *sink, void *stream);
-/* Measurement aid: plain device-to-device copy of `bytes` bytes (both 16-byte aligned); the
- * kernel of known traffic that hardware byte counters are scaled with. */
-int cq_bench_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
-/* Measurement aid: the memory traffic of the tuned quantizer without its arithmetic.  One block per
- * tile of 128 tokens x 128 fp16 values reads the tile's 32 KB of `x_f16` (device, n_tiles * 32 KB,
- * 16-byte aligned) with the quantizer's load pattern and writes `code_bytes_per_tile` (a multiple
- * of 16) to `codes` (device, 16-byte aligned) and `meta_bytes_per_tile` (a multiple of 4) to `meta`
- * (device, 4-byte aligned), both tile after tile.  What is written is meaningless.  CQ_ERR_NULL for
- * null pointers, CQ_ERR_ALIGN for misaligned ones, CQ_ERR_SHAPE for sizes that are not such
- * multiples. */
-int cq_bench_tile_traffic(const void *x_f16, void *codes, void *meta, size_t n_tiles,
-                          int code_bytes_per_tile, int meta_bytes_per_tile, void *stream);
 
 /* Text for a cq_status value; never NULL. */
 const char *cq_status_string(int status);

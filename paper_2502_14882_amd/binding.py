@@ -59,20 +59,27 @@ def lib() -> ctypes.CDLL:
         L.cq_quantize_kv.restype = ctypes.c_int
         L.cq_quantize_kv.argtypes = [P(CqLayout), V, V, P(CqQTensor), P(CqQTensor), V]
         L.cq_decode_workspace_bytes.restype = ctypes.c_size_t
-        L.cq_decode_workspace_bytes.argtypes = [P(CqLayout), I]
+        L.cq_decode_workspace_bytes.argtypes = [P(CqLayout), I, P(CqCalib)]
         L.cq_decode_attn.restype = ctypes.c_int
         L.cq_decode_attn.argtypes = [P(CqLayout), V, P(CqQTensor), P(CqQTensor), V, V, I, I,
                                      P(CqCalib), ctypes.c_float, V, V, ctypes.c_size_t, V]
         L.cq_append_text_kv.restype = ctypes.c_int
         L.cq_append_text_kv.argtypes = [P(CqLayout), V, V, I, I, V, V, V]
+        L.cq_append_text_kv_devlen.restype = ctypes.c_int
+        L.cq_append_text_kv_devlen.argtypes = [P(CqLayout), V, V, V, I, V, V, V]
+        L.cq_decode_attn_devlen.restype = ctypes.c_int
+        L.cq_decode_attn_devlen.argtypes = [P(CqLayout), V, P(CqQTensor), P(CqQTensor), V, V, V, I, I,
+                                            P(CqCalib), ctypes.c_float, V, V, ctypes.c_size_t, V]
         L.cq_tau_search_workspace_bytes.restype = ctypes.c_size_t
         L.cq_tau_search_workspace_bytes.argtypes = [P(CqLayout), I, I, I]
         L.cq_tau_search.restype = ctypes.c_int
         L.cq_tau_search.argtypes = [P(CqLayout), V, V, P(CqQTensor), V, I, I,
                                     P(ctypes.c_float), I, P(ctypes.c_float), I, ctypes.c_float, V, V,
                                     ctypes.c_size_t, V]
-        L.cq_set_kernel_path.restype = ctypes.c_int
-        L.cq_set_kernel_path.argtypes = [ctypes.c_int]
+        L.cq_bench_set_kernel_path.restype = ctypes.c_int
+        L.cq_bench_set_kernel_path.argtypes = [ctypes.c_int]
+        L.cq_bench_set_decode_chunks.restype = ctypes.c_int
+        L.cq_bench_set_decode_chunks.argtypes = [ctypes.c_int]
         L.cq_bench_stream_read.restype = ctypes.c_int
         L.cq_bench_stream_read.argtypes = [V, ctypes.c_size_t, V, V]
         L.cq_bench_stream_copy.restype = ctypes.c_int
@@ -157,8 +164,36 @@ def cq_quantize_kv(layout: CqLayout, k: Optional[torch.Tensor], v: Optional[torc
     return k_out, v_out
 
 
-def cq_decode_workspace_bytes(layout: CqLayout, n_text: int) -> int:
-    return int(lib().cq_decode_workspace_bytes(ctypes.byref(layout), int(n_text)))
+def cq_decode_workspace_bytes(layout: CqLayout, n_text: int, calib: Optional[CqCalib] = None) -> int:
+    return int(lib().cq_decode_workspace_bytes(ctypes.byref(layout), int(n_text),
+                                               ctypes.byref(calib) if calib is not None else None))
+
+
+def _check_decode_tensors(layout: CqLayout, q, k_text, v_text, out) -> int:
+    """Shapes against the layout (a mismatch would be an out-of-bounds read on the device);
+    returns the tail's capacity."""
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    assert tuple(q.shape) == (layout.batch, layout.n_q_heads, layout.head_dim), \
+        "q is %s, the layout says %s" % (tuple(q.shape), (layout.batch, layout.n_q_heads, layout.head_dim))
+    assert out.dtype == torch.float16 and out.is_contiguous() and out.shape == q.shape
+    if k_text is None:
+        assert v_text is None
+        return 0
+    assert k_text.dtype == torch.float16 and k_text.is_contiguous()
+    assert v_text is not None and v_text.dtype == torch.float16 and v_text.is_contiguous()
+    assert v_text.shape == k_text.shape and k_text.dim() == 4
+    assert tuple(k_text.shape[:2]) == (layout.batch, layout.n_kv_heads) and \
+        k_text.shape[3] == layout.head_dim, "text tail is %s" % (tuple(k_text.shape),)
+    return int(k_text.shape[2])
+
+
+def _check_qtensor(layout: CqLayout, t: "QTensor", axis: int, group: int, what: str) -> None:
+    want = (layout.batch, layout.n_kv_heads, layout.n_vis, layout.head_dim * layout.bits // 32)
+    assert tuple(t.codes.shape) == want and t.codes.is_contiguous(), "%s codes are %s" % (what, tuple(t.codes.shape))
+    meta = _meta_shape(layout, axis, group)
+    assert tuple(t.scale.shape) == meta and tuple(t.min.shape) == meta, "%s parameters are %s" % (what, tuple(t.scale.shape))
+    assert t.scale.dtype == torch.float32 and t.min.dtype == torch.float16
+    assert t.scale.is_contiguous() and t.min.is_contiguous()
 
 
 def make_calib(mode=CQ_CALIB_NONE, tau1=0.0, tau2=0.0, gamma=0.0, delta=0.0) -> CqCalib:
@@ -171,17 +206,16 @@ def cq_decode_attn(layout: CqLayout, q: torch.Tensor, k: Optional[QTensor], v: O
                    out: Optional[torch.Tensor] = None,
                    workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     """One decode step; returns out [B, Hq, d] fp16 (allocated here unless given)."""
-    assert q.dtype == torch.float16 and q.is_contiguous()
     if out is None:
         out = torch.empty_like(q)
+    n_text_cap = _check_decode_tensors(layout, q, k_text, v_text, out)
+    assert 0 <= n_text <= n_text_cap
+    if layout.n_vis > 0:
+        _check_qtensor(layout, k, layout.k_axis, layout.k_group, "key")
+        _check_qtensor(layout, v, layout.v_axis, layout.v_group, "value")
     if workspace is None:
-        workspace = torch.empty(cq_decode_workspace_bytes(layout, n_text), dtype=torch.uint8,
+        workspace = torch.empty(cq_decode_workspace_bytes(layout, n_text, calib), dtype=torch.uint8,
                                 device=q.device)
-    n_text_cap = 0
-    if k_text is not None:
-        assert k_text.dtype == torch.float16 and k_text.is_contiguous()
-        assert v_text is not None and v_text.shape == k_text.shape and v_text.is_contiguous()
-        n_text_cap = k_text.shape[2]
     ks = k.c_struct() if k is not None else None
     vs = v.c_struct() if v is not None else None
     _check(lib().cq_decode_attn(
@@ -194,16 +228,66 @@ def cq_decode_attn(layout: CqLayout, q: torch.Tensor, k: Optional[QTensor], v: O
     return out
 
 
+def cq_decode_attn_devlen(layout: CqLayout, q: torch.Tensor, k: Optional[QTensor],
+                          v: Optional[QTensor], k_text: torch.Tensor, v_text: torch.Tensor,
+                          n_text_dev: torch.Tensor, n_text_max: int,
+                          calib: Optional[CqCalib] = None, softmax_scale: float = 0.0,
+                          out: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """cq_decode_attn with the tail length read from the device int32 tensor n_text_dev
+    (n_text_max is the host's bound of it)."""
+    if out is None:
+        out = torch.empty_like(q)
+    n_text_cap = _check_decode_tensors(layout, q, k_text, v_text, out)
+    assert n_text_dev.dtype == torch.int32 and n_text_dev.numel() == 1 and n_text_dev.device == q.device
+    assert 0 <= n_text_max <= n_text_cap
+    if layout.n_vis > 0:
+        _check_qtensor(layout, k, layout.k_axis, layout.k_group, "key")
+        _check_qtensor(layout, v, layout.v_axis, layout.v_group, "value")
+    if workspace is None:
+        workspace = torch.empty(cq_decode_workspace_bytes(layout, n_text_max, calib),
+                                dtype=torch.uint8, device=q.device)
+    ks = k.c_struct() if k is not None else None
+    vs = v.c_struct() if v is not None else None
+    _check(lib().cq_decode_attn_devlen(
+        ctypes.byref(layout), _ptr(q),
+        ctypes.byref(ks) if ks is not None else None,
+        ctypes.byref(vs) if vs is not None else None,
+        _ptr(k_text), _ptr(v_text), _ptr(n_text_dev), int(n_text_max), int(n_text_cap),
+        ctypes.byref(calib) if calib is not None else None, float(softmax_scale),
+        _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(q)))
+    return out
+
+
+def _check_append_tensors(layout: CqLayout, k_text, v_text, k_new, v_new) -> None:
+    for t in (k_text, v_text, k_new, v_new):
+        assert t.dtype == torch.float16 and t.is_contiguous()
+    assert k_text.shape == v_text.shape and k_new.shape == v_new.shape
+    B, H, d = layout.batch, layout.n_kv_heads, layout.head_dim
+    assert tuple(k_text.shape[:2]) == (B, H) and k_text.shape[3] == d
+    assert tuple(k_new.shape) == (B, H, 1, d), "new token is %s" % (tuple(k_new.shape),)
+
+
 def cq_append_text_kv(layout: CqLayout, k_text: torch.Tensor, v_text: torch.Tensor, n_text: int,
                       k_new: torch.Tensor, v_new: torch.Tensor) -> int:
     """Write one new token per sequence, k_new / v_new [B, Hkv, 1, d], to slot n_text of the fp16
     tails [B, Hkv, cap, d] (in place); returns the new n_text."""
-    for t in (k_text, v_text, k_new, v_new):
-        assert t.dtype == torch.float16 and t.is_contiguous()
-    assert k_text.shape == v_text.shape and k_new.shape == v_new.shape
+    _check_append_tensors(layout, k_text, v_text, k_new, v_new)
     _check(lib().cq_append_text_kv(ctypes.byref(layout), _ptr(k_text), _ptr(v_text), int(n_text),
                                    int(k_text.shape[2]), _ptr(k_new), _ptr(v_new), _stream(k_text)))
     return int(n_text) + 1
+
+
+def cq_append_text_kv_devlen(layout: CqLayout, k_text: torch.Tensor, v_text: torch.Tensor,
+                             n_text_dev: torch.Tensor, k_new: torch.Tensor,
+                             v_new: torch.Tensor) -> None:
+    """The same with the tail length in the device int32 tensor n_text_dev, which the call
+    increments on the device (nothing happens when the tail is full)."""
+    _check_append_tensors(layout, k_text, v_text, k_new, v_new)
+    assert n_text_dev.dtype == torch.int32 and n_text_dev.numel() == 1 and n_text_dev.device == k_text.device
+    _check(lib().cq_append_text_kv_devlen(ctypes.byref(layout), _ptr(k_text), _ptr(v_text),
+                                          _ptr(n_text_dev), int(k_text.shape[2]), _ptr(k_new),
+                                          _ptr(v_new), _stream(k_text)))
 
 
 def cq_tau_search_workspace_bytes(layout: CqLayout, n_text: int, n_tau1: int, n_tau2: int) -> int:
@@ -258,8 +342,18 @@ def cq_bench_stream_copy(dst: torch.Tensor, src: torch.Tensor, nbytes: int) -> N
     _check(lib().cq_bench_stream_copy(dst.data_ptr(), src.data_ptr(), int(nbytes), _stream(src)))
 
 
-def cq_set_kernel_path(path: int) -> int:
-    r = lib().cq_set_kernel_path(int(path))
+def cq_bench_set_kernel_path(path: int) -> int:
+    """Test / benchmark switch (cq_bench.h), thread-local: returns the previous path."""
+    r = lib().cq_bench_set_kernel_path(int(path))
+    if r < 0:
+        _check(r)
+    return r
+
+
+def cq_bench_set_decode_chunks(n_chunks: int) -> int:
+    """Test / benchmark switch (cq_bench.h), thread-local: at least n_chunks chunks per row of the
+    tuned decode (0 = automatic); returns the previous value."""
+    r = lib().cq_bench_set_decode_chunks(int(n_chunks))
     if r < 0:
         _check(r)
     return r

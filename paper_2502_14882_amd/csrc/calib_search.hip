@@ -109,7 +109,7 @@ hipError_t launch_tau_search(const DecodeShape& s, const void* q, const void* k_
   float* minmax_x = workspace + wl.minmax_x;
   double* row_mse = reinterpret_cast<double*>(workspace + wl.row_mse);
   // logits on the quantized keys plus the text tail
-  hipError_t e = launch_scores_generic(s, q, k, k_text, softmax_scale, logits_q, minmax_q, stream);
+  hipError_t e = launch_scores_generic(s, q, k, k_text, nullptr, softmax_scale, logits_q, minmax_q, stream);
   if (e != hipSuccess) return e;
   // logits on the exact keys: the same kernel sees them as a 16-bit tail of n_vis tokens
   DecodeShape x = s;
@@ -120,7 +120,7 @@ hipError_t launch_tau_search(const DecodeShape& s, const void* q, const void* k_
   x.n_text_chunks = ceil_div(s.n_vis, kTextChunk);
   x.n_chunks = x.n_text_chunks;
   static const cq_qtensor_t kNone = {nullptr, nullptr, nullptr};
-  e = launch_scores_generic(x, q, kNone, k_exact, softmax_scale, logits_x, minmax_x, stream);
+  e = launch_scores_generic(x, q, kNone, k_exact, nullptr, softmax_scale, logits_x, minmax_x, stream);
   if (e != hipSuccess) return e;
   TauGrid grid;
   grid.n_pairs = n_tau1 * n_tau2;

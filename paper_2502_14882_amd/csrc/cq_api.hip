@@ -1,6 +1,5 @@
 // Host side of libcq: argument validation, kernel-path selection, status strings.
 // Every check here runs before the first HIP call, so a rejected call launches nothing.
-#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -11,7 +10,9 @@
 namespace {
 
 thread_local char g_last_error[256] = "";
-std::atomic<int> g_kernel_path{CQ_PATH_AUTO};
+// test / benchmark switches (cq_bench.h): per thread, never touched by the product calls
+thread_local int g_kernel_path = CQ_PATH_AUTO;
+thread_local int g_decode_chunks = 0;
 
 int fail(int status, const char* fmt, ...) {
   va_list ap;
@@ -38,7 +39,7 @@ int check_group(const char* which, int axis, int group, int n_vis, int d) {
   return CQ_OK;
 }
 
-int check_layout(const cq_layout_t* L, bool need_q_heads) {
+int check_layout(const cq_layout_t* L, bool need_q_heads, bool need_values = true) {
   if (!L) return fail(CQ_ERR_NULL, "layout is NULL");
   if (L->batch < 1 || L->n_kv_heads < 1)
     return fail(CQ_ERR_SHAPE, "batch=%d and n_kv_heads=%d must be >= 1", L->batch, L->n_kv_heads);
@@ -52,8 +53,10 @@ int check_layout(const cq_layout_t* L, bool need_q_heads) {
     return fail(CQ_ERR_UNSUPPORTED, "bits=%d not in {1, 2, 4, 8}", L->bits);
   int rc = check_group("k", L->k_axis, L->k_group, L->n_vis, L->head_dim);
   if (rc != CQ_OK) return rc;
-  rc = check_group("v", L->v_axis, L->v_group, L->n_vis, L->head_dim);
-  if (rc != CQ_OK) return rc;
+  if (need_values) {
+    rc = check_group("v", L->v_axis, L->v_group, L->n_vis, L->head_dim);
+    if (rc != CQ_OK) return rc;
+  }
   const double elems = (double)L->batch * L->n_kv_heads * (double)L->n_vis * L->head_dim;
   if (elems >= 9.0e18) return fail(CQ_ERR_SHAPE, "tensor too large");
   return CQ_OK;
@@ -99,11 +102,136 @@ __global__ void __launch_bounds__(256) append_text_kernel(uint4* k_text, uint4* 
   k_text[dst] = k_new[i];
   v_text[dst] = v_new[i];
 }
+// The same with the tail length in device memory: every thread reads it before anyone changes it
+// (the increment is a launch of its own, ordered behind this one on the stream).
+__global__ void __launch_bounds__(256) append_text_devlen_kernel(uint4* k_text, uint4* v_text, const uint4* k_new,
+                                                                 const uint4* v_new, int rows,
+                                                                 const int32_t* n_text_dev, int n_text_cap,
+                                                                 int vec_per_token) {
+  const int n_text = *n_text_dev;
+  if (n_text < 0 || n_text >= n_text_cap) return;          // full tail: nothing is written
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * vec_per_token) return;
+  const int row = i / vec_per_token, c = i % vec_per_token;
+  const size_t dst = ((size_t)row * n_text_cap + n_text) * vec_per_token + c;
+  k_text[dst] = k_new[i];
+  v_text[dst] = v_new[i];
+}
+__global__ void bump_tail_length_kernel(int32_t* n_text_dev, int n_text_cap) {
+  const int n = *n_text_dev;
+  if (n >= 0 && n < n_text_cap) *n_text_dev = n + 1;
+}
+
+// Everything cq_decode_attn* checks and decides on the host before the first HIP call.
+struct DecodeCall {
+  cq::DecodeShape shape;
+  cq::Calib calib;
+  float softmax_scale;
+  bool tuned;               // the tuned kernels run (else the shape-agnostic ones)
+  cq::FusedPlan plan;       // valid when tuned
+  cq::Workspace generic_ws; // valid when !tuned
+  size_t ws_bytes;          // scratch the selected kernels touch
+};
+
+int check_calib(const cq_calib_t* calib, cq::Calib* c) {
+  *c = cq::Calib{CQ_CALIB_NONE, 0.f, 0.f, 0.f, 0.f};
+  if (!calib) return CQ_OK;
+  if (calib->mode != CQ_CALIB_NONE && calib->mode != CQ_CALIB_DYNAMIC && calib->mode != CQ_CALIB_FIXED)
+    return fail(CQ_ERR_UNSUPPORTED, "calib mode %d is not a CQ_CALIB_* value", calib->mode);
+  c->mode = calib->mode;
+  if (c->mode != CQ_CALIB_NONE) {
+    if (!std::isfinite(calib->tau1) || !std::isfinite(calib->tau2))
+      return fail(CQ_ERR_SHAPE, "tau1 and tau2 must be finite");
+    c->tau1 = calib->tau1;
+    c->tau2 = calib->tau2;
+  }
+  if (c->mode == CQ_CALIB_FIXED) {
+    if (!std::isfinite(calib->gamma) || !std::isfinite(calib->delta) || !(calib->delta > calib->gamma))
+      return fail(CQ_ERR_SHAPE, "CQ_CALIB_FIXED needs finite delta > gamma");
+    c->gamma = calib->gamma;
+    c->delta = calib->delta;
+  }
+  return CQ_OK;
+}
+
+// Kernel selection and scratch size for a valid layout: one plan per call, used by the size query,
+// by the argument check and by the launch.
+int select_kernels(const cq_layout_t* L, int n_text, int n_text_cap, DecodeCall* call) {
+  call->shape = make_shape(L, n_text, n_text_cap);
+  call->plan = cq::make_fused_plan(call->shape, g_decode_chunks);
+  if (g_kernel_path == CQ_PATH_TUNED && !call->plan.ok)
+    return fail(CQ_ERR_UNSUPPORTED, "no tuned decode kernel for this layout");
+  call->tuned = g_kernel_path != CQ_PATH_GENERIC && call->plan.ok;
+  call->generic_ws = cq::workspace_layout(L->batch, L->n_q_heads, L->head_dim, L->n_vis, n_text);
+  call->ws_bytes = call->tuned ? call->plan.ws_bytes : call->generic_ws.total_bytes;
+  return CQ_OK;
+}
+
+// Argument checks of cq_decode_attn, cq_decode_attn_devlen and the allocation-free variant;
+// n_text is the tail length or (n_text_dev != NULL) the host's bound of it.
+int check_decode(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* k,
+                 const cq_qtensor_t* v, const void* k_text_f16, const void* v_text_f16,
+                 int32_t n_text, int32_t n_text_cap, bool length_on_device,
+                 const cq_calib_t* calib, float softmax_scale, const void* out_f16,
+                 DecodeCall* call) {
+  int rc = check_layout(L, true);
+  if (rc != CQ_OK) return rc;
+  if (!q_f16 || !out_f16) return fail(CQ_ERR_NULL, "q_f16 or out_f16 is NULL");
+  if (!aligned16(q_f16) || !aligned16(out_f16))
+    return fail(CQ_ERR_ALIGN, "q_f16 and out_f16 must be 16-byte aligned");
+  if (n_text < 0 || n_text_cap < n_text)
+    return fail(CQ_ERR_SHAPE, "need 0 <= n_text (%d) <= n_text_cap (%d)", n_text, n_text_cap);
+  if ((long long)L->n_vis + n_text < 1)
+    return fail(CQ_ERR_SHAPE, "nothing to attend to: n_vis + n_text == 0");
+  if (L->n_vis > 0) {
+    if ((rc = check_qtensor("k", k)) != CQ_OK) return rc;
+    if ((rc = check_qtensor("v", v)) != CQ_OK) return rc;
+  }
+  if (n_text > 0 || (length_on_device && n_text_cap > 0)) {
+    if (n_text > 0 && (!k_text_f16 || !v_text_f16))
+      return fail(CQ_ERR_NULL, "n_text=%d but k_text_f16 or v_text_f16 is NULL", n_text);
+    if (!aligned16(k_text_f16) || !aligned16(v_text_f16))
+      return fail(CQ_ERR_ALIGN, "text-tail tensors must be 16-byte aligned");
+  }
+  if ((rc = check_calib(calib, &call->calib)) != CQ_OK) return rc;
+  if (!std::isfinite(softmax_scale) || softmax_scale < 0.f)
+    return fail(CQ_ERR_SHAPE, "softmax_scale must be finite and >= 0");
+  call->softmax_scale = softmax_scale == 0.f ? 1.0f / std::sqrt((float)L->head_dim) : softmax_scale;
+  return select_kernels(L, n_text, n_text_cap, call);
+}
+
+int launch_decode(const DecodeCall& call, const void* q_f16, const cq_qtensor_t* k,
+                  const cq_qtensor_t* v, const void* k_text_f16, const void* v_text_f16,
+                  const int32_t* n_text_dev, void* out_f16, void* workspace, void* stream) {
+  static const cq_qtensor_t kNone = {nullptr, nullptr, nullptr};
+  const cq_qtensor_t& kq = k ? *k : kNone;
+  const cq_qtensor_t& vq = v ? *v : kNone;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const hipError_t e = call.tuned
+      ? cq::launch_decode_fused(call.shape, call.plan, q_f16, kq, vq, k_text_f16, v_text_f16,
+                                n_text_dev, call.calib, call.softmax_scale, out_f16,
+                                static_cast<float*>(workspace), st)
+      : cq::launch_decode_generic(call.shape, q_f16, kq, vq, k_text_f16, v_text_f16, n_text_dev,
+                                  call.calib, call.softmax_scale, out_f16,
+                                  static_cast<float*>(workspace), call.generic_ws, st);
+  if (e != hipSuccess) return hip_fail(e, "decode attention");
+  return CQ_OK;
+}
+
+int check_workspace(const void* workspace, size_t workspace_bytes, size_t need) {
+  if (!workspace) return fail(CQ_ERR_WORKSPACE, "workspace is NULL");
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(CQ_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (workspace_bytes < need)
+    return fail(CQ_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+  return CQ_OK;
+}
+
 }  // namespace
 
 extern "C" {
 
-int cq_version(void) { return 100; }
+int cq_version(void) { return 200; }
 
 const char* cq_last_error(void) { return g_last_error; }
 
@@ -120,15 +248,27 @@ const char* cq_status_string(int status) {
   }
 }
 
-int cq_set_kernel_path(int path) {
+int cq_bench_set_kernel_path(int path) {
   if (path != CQ_PATH_AUTO && path != CQ_PATH_GENERIC && path != CQ_PATH_TUNED)
     return fail(CQ_ERR_UNSUPPORTED, "unknown kernel path %d", path);
-  return g_kernel_path.exchange(path);
+  const int prev = g_kernel_path;
+  g_kernel_path = path;
+  return prev;
 }
 
-size_t cq_decode_workspace_bytes(const cq_layout_t* L, int32_t n_text) {
-  if (check_layout(L, true) != CQ_OK || n_text < 0) return 0;
-  return cq::workspace_layout(L->batch, L->n_q_heads, L->head_dim, L->n_vis, n_text).total_bytes;
+int cq_bench_set_decode_chunks(int n_chunks) {
+  if (n_chunks < 0) return fail(CQ_ERR_SHAPE, "n_chunks=%d must be >= 0", n_chunks);
+  const int prev = g_decode_chunks;
+  g_decode_chunks = n_chunks;
+  return prev;
+}
+
+size_t cq_decode_workspace_bytes(const cq_layout_t* L, int32_t n_text, const cq_calib_t* calib) {
+  cq::Calib c;
+  if (check_layout(L, true) != CQ_OK || n_text < 0 || check_calib(calib, &c) != CQ_OK) return 0;
+  DecodeCall call;
+  if (select_kernels(L, n_text, n_text, &call) != CQ_OK) return 0;
+  return call.ws_bytes;
 }
 
 int cq_quantize_kv(const cq_layout_t* L, const void* k_f16, const void* v_f16,
@@ -149,7 +289,7 @@ int cq_quantize_kv(const cq_layout_t* L, const void* k_f16, const void* v_f16,
     if (!aligned16(v_f16)) return fail(CQ_ERR_ALIGN, "v_f16 must be 16-byte aligned");
   }
   if (L->n_vis == 0) return CQ_OK;
-  const int path = g_kernel_path.load();
+  const int path = g_kernel_path;
   const bool k_tuned = cq::quantize_tuned_supported(L->n_vis, L->head_dim, L->bits, L->k_axis, L->k_group);
   const bool v_tuned = cq::quantize_tuned_supported(L->n_vis, L->head_dim, L->bits, L->v_axis, L->v_group);
   if (path == CQ_PATH_TUNED && ((do_k && !k_tuned) || (do_v && !v_tuned)))
@@ -178,82 +318,34 @@ int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* 
                    int32_t n_text, int32_t n_text_cap, const cq_calib_t* calib,
                    float softmax_scale, void* out_f16, void* workspace, size_t workspace_bytes,
                    void* stream) {
-  int rc = check_layout(L, true);
+  DecodeCall call;
+  int rc = check_decode(L, q_f16, k, v, k_text_f16, v_text_f16, n_text, n_text_cap, false, calib,
+                        softmax_scale, out_f16, &call);
   if (rc != CQ_OK) return rc;
-  if (!q_f16 || !out_f16) return fail(CQ_ERR_NULL, "q_f16 or out_f16 is NULL");
-  if (!aligned16(q_f16) || !aligned16(out_f16))
-    return fail(CQ_ERR_ALIGN, "q_f16 and out_f16 must be 16-byte aligned");
-  if (n_text < 0 || n_text_cap < n_text)
-    return fail(CQ_ERR_SHAPE, "need 0 <= n_text (%d) <= n_text_cap (%d)", n_text, n_text_cap);
-  if ((long long)L->n_vis + n_text < 1)
-    return fail(CQ_ERR_SHAPE, "nothing to attend to: n_vis + n_text == 0");
-  if (L->n_vis > 0) {
-    if ((rc = check_qtensor("k", k)) != CQ_OK) return rc;
-    if ((rc = check_qtensor("v", v)) != CQ_OK) return rc;
-  }
-  if (n_text > 0) {
-    if (!k_text_f16 || !v_text_f16)
-      return fail(CQ_ERR_NULL, "n_text=%d but k_text_f16 or v_text_f16 is NULL", n_text);
-    if (!aligned16(k_text_f16) || !aligned16(v_text_f16))
-      return fail(CQ_ERR_ALIGN, "text-tail tensors must be 16-byte aligned");
-  }
-  cq::Calib c{CQ_CALIB_NONE, 0.f, 0.f, 0.f, 0.f};
-  if (calib) {
-    if (calib->mode != CQ_CALIB_NONE && calib->mode != CQ_CALIB_DYNAMIC &&
-        calib->mode != CQ_CALIB_FIXED)
-      return fail(CQ_ERR_UNSUPPORTED, "calib mode %d is not a CQ_CALIB_* value", calib->mode);
-    c.mode = calib->mode;
-    if (c.mode != CQ_CALIB_NONE) {
-      if (!std::isfinite(calib->tau1) || !std::isfinite(calib->tau2))
-        return fail(CQ_ERR_SHAPE, "tau1 and tau2 must be finite");
-      c.tau1 = calib->tau1;
-      c.tau2 = calib->tau2;
-    }
-    if (c.mode == CQ_CALIB_FIXED) {
-      if (!std::isfinite(calib->gamma) || !std::isfinite(calib->delta) ||
-          !(calib->delta > calib->gamma))
-        return fail(CQ_ERR_SHAPE, "CQ_CALIB_FIXED needs finite delta > gamma");
-      c.gamma = calib->gamma;
-      c.delta = calib->delta;
-    }
-  }
-  if (!std::isfinite(softmax_scale) || softmax_scale < 0.f)
-    return fail(CQ_ERR_SHAPE, "softmax_scale must be finite and >= 0");
-  if (softmax_scale == 0.f) softmax_scale = 1.0f / std::sqrt((float)L->head_dim);
+  if ((rc = check_workspace(workspace, workspace_bytes, call.ws_bytes)) != CQ_OK) return rc;
+  return launch_decode(call, q_f16, k, v, k_text_f16, v_text_f16, nullptr, out_f16, workspace, stream);
+}
 
-  const cq::Workspace wl =
-      cq::workspace_layout(L->batch, L->n_q_heads, L->head_dim, L->n_vis, n_text);
-  if (!workspace) return fail(CQ_ERR_WORKSPACE, "workspace is NULL");
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
-    return fail(CQ_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-  if (workspace_bytes < wl.total_bytes)
-    return fail(CQ_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes,
-                wl.total_bytes);
-
-  const cq::DecodeShape s = make_shape(L, n_text, n_text_cap);
-
-  static const cq_qtensor_t kNone = {nullptr, nullptr, nullptr};
-  const cq_qtensor_t& kq = k ? *k : kNone;
-  const cq_qtensor_t& vq = v ? *v : kNone;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const int path = g_kernel_path.load();
-  const bool tuned_ok = cq::fused_supported(s, workspace_bytes);
-  if (path == CQ_PATH_TUNED && !tuned_ok)
-    return fail(CQ_ERR_UNSUPPORTED, "no tuned decode kernel for this layout");
-  hipError_t e;
-  if (path != CQ_PATH_GENERIC && tuned_ok)
-    e = cq::launch_decode_fused(s, q_f16, kq, vq, k_text_f16, v_text_f16, c, softmax_scale, out_f16,
-                                static_cast<float*>(workspace), workspace_bytes, st);
-  else
-    e = cq::launch_decode_generic(s, q_f16, kq, vq, k_text_f16, v_text_f16, c, softmax_scale,
-                                  out_f16, static_cast<float*>(workspace), wl, st);
-  if (e != hipSuccess) return hip_fail(e, "decode attention");
-  return CQ_OK;
+int cq_decode_attn_devlen(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* k,
+                          const cq_qtensor_t* v, const void* k_text_f16, const void* v_text_f16,
+                          const int32_t* n_text_dev, int32_t n_text_max, int32_t n_text_cap,
+                          const cq_calib_t* calib, float softmax_scale, void* out_f16,
+                          void* workspace, size_t workspace_bytes, void* stream) {
+  if (!n_text_dev) return fail(CQ_ERR_NULL, "n_text_dev is NULL");
+  if ((reinterpret_cast<uintptr_t>(n_text_dev) & 3u) != 0)
+    return fail(CQ_ERR_ALIGN, "n_text_dev must be 4-byte aligned");
+  DecodeCall call;
+  int rc = check_decode(L, q_f16, k, v, k_text_f16, v_text_f16, n_text_max, n_text_cap, true, calib,
+                        softmax_scale, out_f16, &call);
+  if (rc != CQ_OK) return rc;
+  if ((rc = check_workspace(workspace, workspace_bytes, call.ws_bytes)) != CQ_OK) return rc;
+  return launch_decode(call, q_f16, k, v, k_text_f16, v_text_f16, n_text_dev, out_f16, workspace,
+                       stream);
 }
 
 size_t cq_tau_search_workspace_bytes(const cq_layout_t* L, int32_t n_text, int32_t n_tau1,
                                      int32_t n_tau2) {
-  if (check_layout(L, true) != CQ_OK || n_text < 0 || n_tau1 < 1 || n_tau2 < 1 ||
+  if (check_layout(L, true, false) != CQ_OK || n_text < 0 || n_tau1 < 1 || n_tau2 < 1 ||
       (long long)n_tau1 * n_tau2 > cq::kMaxTauPairs)
     return 0;
   return cq::tau_workspace_layout(L->batch, L->n_q_heads, L->n_vis, n_text, n_tau1 * n_tau2)
@@ -265,7 +357,7 @@ int cq_tau_search(const cq_layout_t* L, const void* q_f16, const void* k_exact_f
                   const float* tau1, int32_t n_tau1, const float* tau2, int32_t n_tau2,
                   float softmax_scale, double* mse_out, void* workspace, size_t workspace_bytes,
                   void* stream) {
-  int rc = check_layout(L, true);
+  int rc = check_layout(L, true, false);     // the values play no part
   if (rc != CQ_OK) return rc;
   if (L->n_vis < 1) return fail(CQ_ERR_SHAPE, "no quantized tokens to calibrate: n_vis == 0");
   if (!q_f16 || !k_exact_f16 || !mse_out || !tau1 || !tau2)
@@ -308,9 +400,9 @@ int cq_tau_search(const cq_layout_t* L, const void* q_f16, const void* k_exact_f
   return CQ_OK;
 }
 
-int cq_append_text_kv(const cq_layout_t* L, void* k_text_f16, void* v_text_f16, int32_t n_text,
-                      int32_t n_text_cap, const void* k_new_f16, const void* v_new_f16,
-                      void* stream) {
+static int check_append(const cq_layout_t* L, const void* k_text_f16, const void* v_text_f16,
+                        int32_t n_text_cap, const void* k_new_f16, const void* v_new_f16,
+                        long long* n_vec, int* vec_per_token) {
   int rc = check_layout(L, false);
   if (rc != CQ_OK) return rc;
   if (!k_text_f16 || !v_text_f16 || !k_new_f16 || !v_new_f16)
@@ -318,21 +410,56 @@ int cq_append_text_kv(const cq_layout_t* L, void* k_text_f16, void* v_text_f16, 
   if (!aligned16(k_text_f16) || !aligned16(v_text_f16) || !aligned16(k_new_f16) ||
       !aligned16(v_new_f16))
     return fail(CQ_ERR_ALIGN, "tails and new-token tensors must be 16-byte aligned");
+  if (n_text_cap < 1) return fail(CQ_ERR_SHAPE, "the tail has no capacity: n_text_cap=%d", n_text_cap);
+  const long long rows = (long long)L->batch * L->n_kv_heads;
+  *vec_per_token = L->head_dim * 2 / 16;          // head_dim is a multiple of 32
+  *n_vec = rows * *vec_per_token;
+  if (*n_vec > 0x7fffffffLL) return fail(CQ_ERR_SHAPE, "batch * n_kv_heads * head_dim is too large");
+  return CQ_OK;
+}
+
+int cq_append_text_kv(const cq_layout_t* L, void* k_text_f16, void* v_text_f16, int32_t n_text,
+                      int32_t n_text_cap, const void* k_new_f16, const void* v_new_f16,
+                      void* stream) {
+  long long n;
+  int vec_per_token;
+  int rc = check_append(L, k_text_f16, v_text_f16, n_text_cap > 0 ? n_text_cap : 1, k_new_f16,
+                        v_new_f16, &n, &vec_per_token);
+  if (rc != CQ_OK) return rc;
   if (n_text < 0 || n_text >= n_text_cap)
     return fail(CQ_ERR_SHAPE, "the tail is full or n_text is negative: n_text=%d, n_text_cap=%d",
                 n_text, n_text_cap);
-  const long long rows = (long long)L->batch * L->n_kv_heads;
-  const int vec_per_token = L->head_dim * 2 / 16;          // head_dim is a multiple of 32
-  const long long n = rows * vec_per_token;
-  if (n == 0) return CQ_OK;
-  if (n > 0x7fffffffLL) return fail(CQ_ERR_SHAPE, "batch * n_kv_heads * head_dim is too large");
   append_text_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
                        static_cast<hipStream_t>(stream)>>>(
       static_cast<uint4*>(k_text_f16), static_cast<uint4*>(v_text_f16),
-      static_cast<const uint4*>(k_new_f16), static_cast<const uint4*>(v_new_f16), (int)rows, n_text,
-      n_text_cap, vec_per_token);
+      static_cast<const uint4*>(k_new_f16), static_cast<const uint4*>(v_new_f16),
+      (int)(n / vec_per_token), n_text, n_text_cap, vec_per_token);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(CQ_ERR_HIP, "append_text_kernel: %s", hipGetErrorString(e));
+  return CQ_OK;
+}
+
+int cq_append_text_kv_devlen(const cq_layout_t* L, void* k_text_f16, void* v_text_f16,
+                             int32_t* n_text_dev, int32_t n_text_cap, const void* k_new_f16,
+                             const void* v_new_f16, void* stream) {
+  long long n;
+  int vec_per_token;
+  int rc = check_append(L, k_text_f16, v_text_f16, n_text_cap, k_new_f16, v_new_f16, &n,
+                        &vec_per_token);
+  if (rc != CQ_OK) return rc;
+  if (!n_text_dev) return fail(CQ_ERR_NULL, "n_text_dev is NULL");
+  if ((reinterpret_cast<uintptr_t>(n_text_dev) & 3u) != 0)
+    return fail(CQ_ERR_ALIGN, "n_text_dev must be 4-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  append_text_devlen_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(
+      static_cast<uint4*>(k_text_f16), static_cast<uint4*>(v_text_f16),
+      static_cast<const uint4*>(k_new_f16), static_cast<const uint4*>(v_new_f16),
+      (int)(n / vec_per_token), n_text_dev, n_text_cap, vec_per_token);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(CQ_ERR_HIP, "append_text_devlen_kernel: %s", hipGetErrorString(e));
+  bump_tail_length_kernel<<<dim3(1), dim3(1), 0, st>>>(n_text_dev, n_text_cap);
+  e = hipGetLastError();
+  if (e != hipSuccess) return fail(CQ_ERR_HIP, "bump_tail_length_kernel: %s", hipGetErrorString(e));
   return CQ_OK;
 }
 

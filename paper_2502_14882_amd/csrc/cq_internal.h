@@ -8,6 +8,7 @@
 #include <stdint.h>
 
 #include "cq.h"
+#include "cq_bench.h"
 
 namespace cq {
 
@@ -17,6 +18,8 @@ constexpr int kVisChunk = 512;
 constexpr int kTextChunk = 512;
 
 struct DecodeShape {
+  // n_text: tokens of the fp16 tail that are attended, or - when the length lives in device
+  // memory (n_text_dev below) - the host's upper bound of it, which sizes launches and buffers
   int B, Hq, Hkv, g, d, n_vis, n_text, n_text_cap;
   int bits, k_axis, v_axis, k_group, v_group;
   int n_vis_chunks, n_text_chunks, n_chunks;
@@ -57,16 +60,20 @@ hipError_t launch_quantize_generic(const void* x_f16, const cq_qtensor_t& out, i
                                    int n_vis, int d, int bits, int axis, int group,
                                    hipStream_t stream);
 
+// n_text_dev (all decode launchers): NULL, or a device int32 holding the current tail length; the
+// kernels then attend to min(max(*n_text_dev, 0), s.n_text) text tokens.
 hipError_t launch_decode_generic(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
                                  const cq_qtensor_t& v, const void* k_text, const void* v_text,
-                                 const Calib& calib, float softmax_scale, void* out,
-                                 float* workspace, const Workspace& wl, hipStream_t stream);
+                                 const int32_t* n_text_dev, const Calib& calib,
+                                 float softmax_scale, void* out, float* workspace,
+                                 const Workspace& wl, hipStream_t stream);
 
 // First stage of the shape-agnostic decode on its own: raw logits [B*Hq][n_vis + n_text] and the
 // extrema [B*Hq][n_chunks][2] of every chunk of tokens.
 hipError_t launch_scores_generic(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
-                                 const void* k_text, float softmax_scale, float* logits,
-                                 float* minmax, hipStream_t stream);
+                                 const void* k_text, const int32_t* n_text_dev,
+                                 float softmax_scale, float* logits, float* minmax,
+                                 hipStream_t stream);
 
 // Grid search of the calibration parameters (Sec. 3.2): workspace layout in floats, and launcher.
 constexpr int kMaxTauPairs = 64;
@@ -110,14 +117,25 @@ hipError_t launch_quantize_tuned(const void* x_f16, const cq_qtensor_t& out, int
 hipError_t launch_combine(int n_rows, int n_chunks, int d, const float* partial, void* out,
                           hipStream_t stream);
 
-// Tuned decode for head_dim 128, 1-bit codes, channel-wise keys, per-token values, g <= 8:
-// one fused launch when a workgroup can own a whole row, else extrema pass + partial pass +
-// combine over chunks of the row (workspace: extrema and partials only).
-bool fused_supported(const DecodeShape& s, size_t workspace_bytes);
-hipError_t launch_decode_fused(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
-                               const cq_qtensor_t& v, const void* k_text, const void* v_text,
-                               const Calib& calib, float softmax_scale, void* out,
-                               float* workspace, size_t workspace_bytes, hipStream_t stream);
+// Tuned decode for head_dim 128 (see decode_fused.hip for the layouts it takes): one fused launch
+// when a workgroup can own a whole row, else extrema pass + partial pass + combine over chunks
+// of the row.  The plan is made once per call on the host and says what will run.
+struct FusedPlan {
+  bool ok = false;            // a tuned kernel exists for the shape
+  int nhb = 1;                // blocks of 4 query heads per KV head
+  int n_chunks = 1;           // chunks per row
+  int stride = 0;             // floats between the logit rows of two heads in LDS
+  size_t lds = 0;             // dynamic LDS bytes per workgroup
+  size_t ws_minmax_floats = 0;  // split rows: [B*Hq][n_chunks][2] (offset of the partials)
+  size_t ws_bytes = 256;      // workspace the launches touch (a multiple of 256, >= 256)
+};
+// min_chunks: 0 = the fewest chunks that fit on chip, n >= 1 = at least n (test override)
+FusedPlan make_fused_plan(const DecodeShape& s, int min_chunks);
+hipError_t launch_decode_fused(const DecodeShape& s, const FusedPlan& plan, const void* q,
+                               const cq_qtensor_t& k, const cq_qtensor_t& v, const void* k_text,
+                               const void* v_text, const int32_t* n_text_dev, const Calib& calib,
+                               float softmax_scale, void* out, float* workspace,
+                               hipStream_t stream);
 
 }  // namespace cq
 

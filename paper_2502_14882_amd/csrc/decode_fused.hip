@@ -33,7 +33,6 @@
 #include <atomic>
 #include <cfloat>
 #include <type_traits>
-#include <cstdlib>
 
 #include "cq_internal.h"
 
@@ -62,19 +61,7 @@ constexpr int kRedPerHead = 6;
 // groups in flight are 1-2 % faster than 2 and 4 are 8 % slower (about 1 % faster with groups of
 // 32 tokens, slower with 64), on short or split rows 3 are 3-5 % slower (the kernel's RK
 // parameter); the other rings make no difference.
-#ifndef CQ_RING_K
-#define CQ_RING_K 2
-#endif
-#ifndef CQ_RING_V
-#define CQ_RING_V 2
-#endif
-#ifndef CQ_RING_T
-#define CQ_RING_T 2
-#endif
-#ifndef CQ_RING_TV
-#define CQ_RING_TV 4
-#endif
-constexpr int kRingK = CQ_RING_K, kRingV = CQ_RING_V, kRingT = CQ_RING_T, kRingTV = CQ_RING_TV;
+constexpr int kRingK = 2, kRingV = 2, kRingT = 2, kRingTV = 4;
 static_assert(kRingV % 2 == 0, "value tiles alternate between two LDS buffers");
 constexpr float kLog2e = 1.4426950408889634f;
 // kModeFull: the workgroup owns the whole row and writes `out`.  A row that does not fit LDS, has
@@ -95,6 +82,7 @@ struct FusedArgs {
   const __half* k_text; const __half* v_text;
   __half* out;
   int Hq, Hkv, g, n_vis, n_text, n_text_cap;
+  const int32_t* n_text_dev;   // NULL, or the tail length in device memory (n_text is then its bound)
   int k_group;       // tokens that are processed as one key group (32, 64 or 128)
   int v_group;       // channel-wise values: tokens processed as one value group (64 or 128)
   // Parameters (scale, min) of channel-wise tensors: elements per row, and elements between two
@@ -112,19 +100,8 @@ struct FusedArgs {
   float* ws_minmax;  // split rows: [B*Hq][n_chunks][2] extrema of the visual logits
   float* ws_partial; // split rows: [B*Hq][n_chunks][d + 2] partials (m, l, acc) for the combine
   int calib_mode; float tau1, tau2, gamma, delta, softmax_scale;
-#ifdef CQ_PHASE_CLOCKS
-  long long* clocks;   // [rows][64] time stamps of the phase boundaries (profiling builds only)
-#endif
 };
 
-#ifdef CQ_PHASE_CLOCKS
-#define CQ_CLK(k) do { if (lane == 0 && (wave == 0 || wave == kVisWaves) && a.clocks) \
-    a.clocks[(size_t)row * 64 + (wave ? 16 : 0) + (k)] = wall_clock64(); } while (0)
-#define CQ_CLKW(k) do { if (lane == 0 && a.clocks) a.clocks[(size_t)row * 64 + (k) + wave] = wall_clock64(); } while (0)
-#else
-#define CQ_CLK(k) do { } while (0)
-#define CQ_CLKW(k) do { } while (0)
-#endif
 
 // Load of cache data that the workgroup reads exactly once.  NT marks it non-temporal (measured on
 // a plain streaming read of the same bytes: 6.4-6.6 TB/s against 5.8 TB/s with ordinary loads).
@@ -360,12 +337,13 @@ fused_row_kernel(const FusedArgs a) {
   const int ba = chunk_first(a.tblocks_base, a.tblocks_rem, chunk);
   const int bb = chunk_first(a.tblocks_base, a.tblocks_rem, chunk + 1);
   const int txt0 = ba * 64;
-  const int ntx = a.mode == kModeExtrema ? 0 : max(0, min(a.n_text, bb * 64) - txt0);
+  // the tail length: the host's value, or the device's clamped to it (a growing tail in a replayed graph)
+  const int n_text = a.n_text_dev ? min(max(*a.n_text_dev, 0), a.n_text) : a.n_text;
+  const int ntx = a.mode == kModeExtrema ? 0 : max(0, min(n_text, bb * 64) - txt0);
   const bool vis_wave = wave < kVisWaves;
   const int tw = wave - kVisWaves;            // index among the text waves
   const int n16 = lane & 15, kb = lane >> 4;
 
-  CQ_CLK(0);
   // ---- LDS carve-up
   float* logits = reinterpret_cast<float*>(smem);                       // [kHeads][stride]
   uint8_t* lbytes = smem;
@@ -403,7 +381,6 @@ fused_row_kernel(const FusedArgs a) {
   for (int h = 0; h < kHeads; ++h) qmax[h] = fmaxf(red[2 * h], red[2 * h + 1]) * a.softmax_scale;
   const float qmax_all = fmaxf(fmaxf(qmax[0], qmax[1]), fmaxf(qmax[2], qmax[3]));
   __syncthreads();   // red is reused below
-  CQ_CLK(1);
   // Split row: the chunk extrema of the first pass, which phase 2 needs for the calibration line,
   // are asked for here and arrive during phase 1 (lane 16h + w: head h, chunk w; a lane beyond the
   // live heads or chunks reads a neighbour's pair, which folds in harmlessly or is never used).
@@ -660,8 +637,6 @@ fused_row_kernel(const FusedArgs a) {
       for (int d = 0; d < kRK; ++d)                 // the wave's last groups, already loaded
         if (t + d * kVisWaves < n_groups) do_group(d, t + d * kVisWaves);
     }
-    CQ_CLK(2);
-    CQ_CLKW(32);
     // fold the 16 token lanes of every head
     mn = row_min(mn);     // on the DPP network: no LDS round trips at the end of the phase
     mx = row_max(mx);
@@ -741,15 +716,12 @@ fused_row_kernel(const FusedArgs a) {
         }
       }
     }
-    CQ_CLK(2);
-    CQ_CLKW(32);
 #pragma unroll
     for (int r = 0; r < 4; ++r) tmax[r] = row_max(tmax[r]);
     if (lane == 0)
       for (int r = 0; r < 4; ++r) red[(wave * kHeads + r) * kRedPerHead + 2] = tmax[r];
   }
   __syncthreads();
-  CQ_CLK(3);
   if (a.mode == kModeExtrema) {
     // first pass of a split row: only the extrema of this chunk's visual logits are wanted
     if (tid < gh) {
@@ -1215,8 +1187,6 @@ fused_row_kernel(const FusedArgs a) {
         if (j0 + d * step < nv) m_step(j0 + d * step, d, false);
       Fv = F_acc;
     } }
-    CQ_CLK(4);
-    CQ_CLKW(48);
   } else {
     // text tail.  lane = (token slot kb, channels 8 * n16 .. +7): one 16-byte load covers 8 channels
     // of one token, a wave-wide load covers 4 tokens.  The contraction over tokens runs on the
@@ -1326,11 +1296,8 @@ fused_row_kernel(const FusedArgs a) {
     }
 #pragma unroll
     for (int h = 0; h < kHeads; ++h) lsum[h] = tl[h];
-    CQ_CLK(4);
-    CQ_CLKW(48);
   }
   __syncthreads();    // logits are dead from here on; their LDS becomes the partial buffer
-  CQ_CLK(5);
 
   float* partial = reinterpret_cast<float*>(smem) + (size_t)wave * kHeads * kD;   // [head][channel]
   if (vis_wave) {
@@ -1352,7 +1319,6 @@ fused_row_kernel(const FusedArgs a) {
     for (int h = 0; h < kHeads; ++h)
       *reinterpret_cast<v2f*>(partial + h * kD + 8 * n16 + 2 * kb) = (v2f){ttot[2 * h], ttot[2 * h + 1]};
   }
-  CQ_CLK(7);
   // The per-wave sums of the weights (l) and of the additive value term (m), four heads each: a
   // transposing fold over the wave's rows of lanes with paired swaps (a swap of two values and one
   // add halve both), then one row reduction per register: rows 0..3 of the first register end up
@@ -1378,9 +1344,7 @@ fused_row_kernel(const FusedArgs a) {
       for (int h = 0; h < kHeads; ++h) red[h * kRedPerHead + 5] = mref[h];
     }
   }
-  CQ_CLK(8);
   __syncthreads();
-  CQ_CLK(9);
 
   // ---- epilogue: sum the waves, add the additive value term, normalise, round to fp16
   if (tid < kHeads * kD) {
@@ -1406,15 +1370,10 @@ fused_row_kernel(const FusedArgs a) {
       }
     }
   }
-  CQ_CLK(6);
 }
 
 }  // namespace
 
-#ifdef CQ_PHASE_CLOCKS
-static long long* g_phase_clocks = nullptr;
-extern "C" void cq_debug_set_phase_clocks(void* p) { g_phase_clocks = static_cast<long long*>(p); }
-#endif
 
 size_t fused_lds_bytes(int n_vis_chunk, int n_text_chunk, int k_group, int* stride_out) {
   // text slots are rounded up to whole 64-token blocks (a block's weights are staged in place)
@@ -1433,12 +1392,6 @@ size_t fused_lds_bytes(int n_vis_chunk, int n_text_chunk, int k_group, int* stri
 }
 
 namespace {
-
-struct FusedPlan {
-  bool ok = false;
-  int nhb = 1, n_chunks = 1, stride = 0;
-  size_t lds = 0, ws_minmax_floats = 0, ws_floats = 0;
-};
 
 constexpr int kMaxDevices = 64;
 
@@ -1497,7 +1450,9 @@ void chunk_extent(const DecodeShape& s, int n_chunks, int* nv_max, int* nt_max) 
   }
 }
 
-FusedPlan make_plan(const DecodeShape& shape, size_t workspace_bytes) {
+}  // namespace
+
+FusedPlan make_fused_plan(const DecodeShape& shape, int min_chunks) {
   FusedPlan p;
   bool k_whole, v_whole;
   const DecodeShape s = processing_shape(shape, &k_whole, &v_whole);
@@ -1516,11 +1471,7 @@ FusedPlan make_plan(const DecodeShape& shape, size_t workspace_bytes) {
   // Fewest chunks that fit LDS.  Splitting a row that fits only to fill idle CUs does not pay:
   // every chunk repeats the fixed per-workgroup work and the logits are computed twice
   // (measured on the 128-row configuration: 24 us whole rows, 35 us in 2 chunks, 57 us in 4).
-  int want = 1;
-  if (const char* env = getenv("CQ_DECODE_CHUNKS")) {           // testing / tuning override
-    const int forced = atoi(env);
-    if (forced >= 1) want = forced;
-  }
+  int want = min_chunks >= 1 ? min_chunks : 1;                 // > 1: a test's or a tuner's override
   if (want > max_chunks) want = max_chunks;
   const bool forced = want > 1;
   for (int c = want; c <= max_chunks; ++c) {
@@ -1561,25 +1512,21 @@ FusedPlan make_plan(const DecodeShape& shape, size_t workspace_bytes) {
   if (p.n_chunks > 1 || p.nhb > 1) {
     if (s.n_vis == 0) return p;
     const size_t heads = (size_t)s.B * s.Hq;
+    // chunk extrema of the visual logits (read only with dynamic calibration; 12 KB on the
+    // long-context configuration), then one (m, l, acc[d]) partial per (head, chunk)
     p.ws_minmax_floats = (heads * p.n_chunks * 2 + 63) / 64 * 64;
-    p.ws_floats = p.ws_minmax_floats + heads * p.n_chunks * (size_t)(kD + 2);
-    if (p.ws_floats * sizeof(float) > workspace_bytes) return p;
+    const size_t floats = p.ws_minmax_floats + heads * p.n_chunks * (size_t)(kD + 2);
+    p.ws_bytes = (floats * sizeof(float) + 255) / 256 * 256;
   }
   p.ok = true;
   return p;
 }
 
-}  // namespace
-
-bool fused_supported(const DecodeShape& s, size_t workspace_bytes) {
-  return make_plan(s, workspace_bytes).ok;
-}
-
-hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq_qtensor_t& k,
-                               const cq_qtensor_t& v, const void* k_text, const void* v_text,
-                               const Calib& calib, float softmax_scale, void* out,
-                               float* workspace, size_t workspace_bytes, hipStream_t stream) {
-  const FusedPlan plan = make_plan(shape, workspace_bytes);
+hipError_t launch_decode_fused(const DecodeShape& shape, const FusedPlan& plan, const void* q,
+                               const cq_qtensor_t& k, const cq_qtensor_t& v, const void* k_text,
+                               const void* v_text, const int32_t* n_text_dev, const Calib& calib,
+                               float softmax_scale, void* out, float* workspace,
+                               hipStream_t stream) {
   if (!plan.ok) return hipErrorInvalidValue;
   bool k_whole, v_whole;
   const DecodeShape s = processing_shape(shape, &k_whole, &v_whole);
@@ -1591,7 +1538,7 @@ hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq
   a.v_text = static_cast<const __half*>(v_text);
   a.out = static_cast<__half*>(out);
   a.Hq = s.Hq; a.Hkv = s.Hkv; a.g = s.g; a.n_vis = s.n_vis; a.n_text = s.n_text;
-  a.n_text_cap = s.n_text_cap; a.k_group = s.k_group;
+  a.n_text_cap = s.n_text_cap; a.n_text_dev = n_text_dev; a.k_group = s.k_group;
   a.v_group = s.v_group; a.unit = chunk_unit(s);
   a.k_prow = k_whole ? kD : s.n_vis / s.k_group * kD;
   a.k_pstride = k_whole ? 0 : kD;
@@ -1607,9 +1554,6 @@ hipError_t launch_decode_fused(const DecodeShape& shape, const void* q, const cq
   a.nhb = plan.nhb;
   a.ws_minmax = workspace;
   a.ws_partial = workspace ? workspace + plan.ws_minmax_floats : nullptr;
-#ifdef CQ_PHASE_CLOCKS
-  a.clocks = g_phase_clocks;
-#endif
   void (*kern)(const FusedArgs) = nullptr;
   int slot = 0;
   const bool vch = s.v_axis == CQ_AXIS_CHANNEL;

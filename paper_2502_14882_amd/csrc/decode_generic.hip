@@ -46,17 +46,20 @@ __device__ inline float dequant(const QParams& t, size_t row, int n_vis, int d, 
 // grid.x = rows * n_chunks.  Thread per token of the chunk.
 __global__ void __launch_bounds__(kScoreThreads)
 scores_kernel(DecodeShape s, const __half* __restrict__ q, QParams k,
-              const __half* __restrict__ k_text, float softmax_scale, float* __restrict__ logits,
-              float* __restrict__ minmax) {
+              const __half* __restrict__ k_text, const int32_t* __restrict__ n_text_dev,
+              float softmax_scale, float* __restrict__ logits, float* __restrict__ minmax) {
   __shared__ float qs[kHeadBlock][kMaxDim];
   __shared__ float red_min[kScoreThreads], red_max[kScoreThreads];
+  // rows of the logit array are laid out for the host's bound of the tail length; a length held
+  // in device memory only shortens what is computed (chunks past it stay empty)
+  const int n_all = s.n_vis + s.n_text;
+  if (n_text_dev) s.n_text = min(max(*n_text_dev, 0), s.n_text);
   const int chunk = blockIdx.x % s.n_chunks;
   const size_t row = blockIdx.x / s.n_chunks;   // b * Hkv + kvh
   const int b = (int)(row / s.Hkv), kvh = (int)(row % s.Hkv);
   const bool is_text = chunk >= s.n_vis_chunks;
   const int j0 = is_text ? (chunk - s.n_vis_chunks) * kTextChunk : chunk * kVisChunk;
   const int j1 = is_text ? min(j0 + kTextChunk, s.n_text) : min(j0 + kVisChunk, s.n_vis);
-  const int n_all = s.n_vis + s.n_text;
   const int per = 32 / s.bits;
 
   for (int hb = 0; hb < s.g; hb += kHeadBlock) {
@@ -117,18 +120,20 @@ scores_kernel(DecodeShape s, const __half* __restrict__ q, QParams k,
 }
 
 // grid.x = rows * n_chunks.  Thread per output channel.
-__global__ void pv_kernel(DecodeShape s, QParams v, const __half* __restrict__ v_text, Calib cal,
+__global__ void pv_kernel(DecodeShape s, QParams v, const __half* __restrict__ v_text,
+                          const int32_t* __restrict__ n_text_dev, Calib cal,
                           const float* __restrict__ logits, const float* __restrict__ minmax,
                           float* __restrict__ partial) {
   __shared__ float p[kHeadBlock][kPvTile];
   __shared__ float slope_s[kHeadBlock], gamma_s[kHeadBlock], shift_s[kHeadBlock], m_s[kHeadBlock];
+  const int n_all = s.n_vis + s.n_text;       // row pitch of the logits: the host's bound
+  if (n_text_dev) s.n_text = min(max(*n_text_dev, 0), s.n_text);
   const int chunk = blockIdx.x % s.n_chunks;
   const size_t row = blockIdx.x / s.n_chunks;
   const int b = (int)(row / s.Hkv), kvh = (int)(row % s.Hkv);
   const bool is_text = chunk >= s.n_vis_chunks;
   const int j0 = is_text ? (chunk - s.n_vis_chunks) * kTextChunk : chunk * kVisChunk;
   const int j1 = is_text ? min(j0 + kTextChunk, s.n_text) : min(j0 + kVisChunk, s.n_vis);
-  const int n_all = s.n_vis + s.n_text;
   const int c = threadIdx.x;
   const int per = 32 / s.bits;
 
@@ -156,7 +161,9 @@ __global__ void pv_kernel(DecodeShape s, QParams v, const __half* __restrict__ v
       const float clo = slope * (mm[2 * chunk] - gamma) + shift;
       const float chi = slope * (mm[2 * chunk + 1] - gamma) + shift;
       slope_s[c] = slope; gamma_s[c] = gamma; shift_s[c] = shift;
-      m_s[c] = fmaxf(clo, chi);     // the map is monotone, so an end point is the chunk maximum
+      // the map is monotone, so an end point is the chunk maximum; a chunk without tokens (beyond
+      // a tail length read from device memory) must not set the reference point of the combine
+      m_s[c] = j1 > j0 ? fmaxf(clo, chi) : -FLT_MAX;
     }
     __syncthreads();
     float acc[kHeadBlock], l[kHeadBlock];
@@ -244,21 +251,23 @@ hipError_t launch_combine(int n_rows, int n_chunks, int d, const float* partial,
 }
 
 hipError_t launch_scores_generic(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
-                                 const void* k_text, float softmax_scale, float* logits,
-                                 float* minmax, hipStream_t stream) {
+                                 const void* k_text, const int32_t* n_text_dev,
+                                 float softmax_scale, float* logits, float* minmax,
+                                 hipStream_t stream) {
   const size_t blocks = (size_t)s.B * s.Hkv * (size_t)s.n_chunks;
   if (blocks > 0x7fffffffu) return hipErrorInvalidConfiguration;
   QParams kp{k.codes, k.scale, k.min, s.k_axis, s.k_group};
   scores_kernel<<<dim3((unsigned)blocks), dim3(kScoreThreads), 0, stream>>>(
-      s, static_cast<const __half*>(q), kp, static_cast<const __half*>(k_text), softmax_scale,
-      logits, minmax);
+      s, static_cast<const __half*>(q), kp, static_cast<const __half*>(k_text), n_text_dev,
+      softmax_scale, logits, minmax);
   return hipGetLastError();
 }
 
 hipError_t launch_decode_generic(const DecodeShape& s, const void* q, const cq_qtensor_t& k,
                                  const cq_qtensor_t& v, const void* k_text, const void* v_text,
-                                 const Calib& calib, float softmax_scale, void* out,
-                                 float* workspace, const Workspace& wl, hipStream_t stream) {
+                                 const int32_t* n_text_dev, const Calib& calib,
+                                 float softmax_scale, void* out, float* workspace,
+                                 const Workspace& wl, hipStream_t stream) {
   const size_t blocks = (size_t)s.B * s.Hkv * (size_t)s.n_chunks;
   if (blocks > 0x7fffffffu || (size_t)s.B * s.Hq > 0x7fffffffu) return hipErrorInvalidConfiguration;
   QParams kp{k.codes, k.scale, k.min, s.k_axis, s.k_group};
@@ -267,12 +276,12 @@ hipError_t launch_decode_generic(const DecodeShape& s, const void* q, const cq_q
   float* minmax = workspace + wl.minmax;
   float* partial = workspace + wl.partial;
   scores_kernel<<<dim3((unsigned)blocks), dim3(kScoreThreads), 0, stream>>>(
-      s, static_cast<const __half*>(q), kp, static_cast<const __half*>(k_text), softmax_scale,
-      logits, minmax);
+      s, static_cast<const __half*>(q), kp, static_cast<const __half*>(k_text), n_text_dev,
+      softmax_scale, logits, minmax);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   pv_kernel<<<dim3((unsigned)blocks), dim3(s.d), 0, stream>>>(
-      s, vp, static_cast<const __half*>(v_text), calib, logits, minmax, partial);
+      s, vp, static_cast<const __half*>(v_text), n_text_dev, calib, logits, minmax, partial);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   combine_kernel<<<dim3((unsigned)((size_t)s.B * s.Hq)), dim3(s.d), 0, stream>>>(

@@ -28,3 +28,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def decode_chunks():
+    """Setter of the library's thread-local test switch "at least n chunks per row of the tuned
+    decode" (cq_bench.h); automatic again after the test."""
+    from paper_2502_14882_amd import binding as cq
+    yield cq.cq_bench_set_decode_chunks
+    cq.cq_bench_set_decode_chunks(0)

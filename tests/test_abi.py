@@ -13,20 +13,49 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 FAKE = 0x10000     # aligned, non-NULL, never touched
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "cq.h")).read()
+def _declared_functions(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(cq_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(cq_[a-z_0-9]+)\s*\(", text)))
+
+
+# the product ABI: the two operations of the hot path with their size query, the steps either
+# side of them, status reporting, and the entry point for callers that cannot allocate
+PRODUCT_ABI = ["cq_append_text_kv", "cq_append_text_kv_devlen", "cq_decode_attn",
+               "cq_decode_attn_devlen", "cq_decode_workspace_bytes",
+               "cq_last_error", "cq_quantize_kv", "cq_status_string", "cq_tau_search",
+               "cq_tau_search_workspace_bytes", "cq_version"]
+BENCH_ABI = ["cq_bench_set_decode_chunks", "cq_bench_set_kernel_path", "cq_bench_stream_copy",
+             "cq_bench_stream_read", "cq_bench_tile_traffic"]
 
 
 def test_library_exports_every_declared_symbol():
-    names = _declared_functions()
-    assert {"cq_quantize_kv", "cq_decode_attn", "cq_decode_workspace_bytes", "cq_status_string",
-            "cq_last_error", "cq_version", "cq_set_kernel_path"} <= set(names)
+    assert _declared_functions("cq.h") == sorted(PRODUCT_ABI)
+    assert _declared_functions("cq_bench.h") == sorted(BENCH_ABI)
     L = cq.lib()
-    for n in names:
+    for n in PRODUCT_ABI + BENCH_ABI:
         assert hasattr(L, n), n
-    assert cq.cq_version() >= 100
+    assert cq.cq_version() >= 200
+
+
+def test_library_exports_nothing_else():
+    """The dynamic symbol table holds the declared cq_* functions and no other cq_* name (no debug
+    hooks, no process-wide switches)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", cq.LIB_PATH], capture_output=True, text=True)
+    if out.returncode != 0:
+        pytest.skip("nm is not available")
+    names = sorted({l.split()[-1] for l in out.stdout.splitlines() if l.split() and l.split()[-1].startswith("cq_")})
+    assert names == sorted(PRODUCT_ABI + BENCH_ABI)
+
+
+def test_library_reads_no_environment_variable():
+    """No getenv in the library: a stray variable cannot change what a decode call launches."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--undefined-only", cq.LIB_PATH], capture_output=True, text=True)
+    if out.returncode != 0:
+        pytest.skip("nm is not available")
+    assert not [l for l in out.stdout.splitlines() if "getenv" in l]
 
 
 def test_struct_sizes_match_header():
@@ -79,7 +108,7 @@ def test_decode_argument_errors():
     assert _decode(lay, n_text=-1) == cq.CQ_ERR_SHAPE
     assert _decode(lay, ws=None) == cq.CQ_ERR_WORKSPACE
     assert _decode(lay, ws=FAKE + 16) == cq.CQ_ERR_WORKSPACE
-    assert _decode(lay, ws_bytes=1024) == cq.CQ_ERR_WORKSPACE
+    assert _decode(lay, ws_bytes=16) == cq.CQ_ERR_WORKSPACE
     assert _decode(lay, out=FAKE + 8) == cq.CQ_ERR_ALIGN
     assert _decode(lay, calib=cq.make_calib(9)) == cq.CQ_ERR_UNSUPPORTED
     assert _decode(lay, calib=cq.make_calib(cq.CQ_CALIB_FIXED, 1, 2, 3.0, 3.0)) == cq.CQ_ERR_SHAPE
@@ -131,6 +160,9 @@ def test_tau_search_argument_errors():
     assert call(ws=None) == cq.CQ_ERR_WORKSPACE
     assert call(ws_bytes=need - 256) == cq.CQ_ERR_WORKSPACE
     assert call(lay=cq.make_layout(2, 8, 2, 128, 0)) == cq.CQ_ERR_SHAPE    # nothing quantized
+    # the values play no part: an invalid value group is not an error here, an invalid key group is
+    assert cq.cq_tau_search_workspace_bytes(cq.make_layout(2, 8, 2, 128, 256, v_group=48), 16, 4, 4) == need
+    assert call(lay=cq.make_layout(2, 8, 2, 128, 256, k_group=96)) == cq.CQ_ERR_SHAPE
 
 
 def test_measurement_aid_argument_errors():
@@ -146,22 +178,83 @@ def test_measurement_aid_argument_errors():
     assert f(FAKE, FAKE, FAKE, 0, 2048, 768, None) == cq.CQ_OK          # nothing to do, no launch
 
 
-def test_workspace_size_rule():
-    lay = cq.make_layout(2, 8, 2, 128, 1024)
-    n = cq.cq_decode_workspace_bytes(lay, 32)
-    assert n > 0 and n % 256 == 0
-    # it at least holds one fp32 logit per (batch, query head, token)
-    assert n >= 2 * 8 * (1024 + 32) * 4
-    assert cq.cq_decode_workspace_bytes(cq.make_layout(2, 8, 2, 100, 1024), 32) == 0
-    bigger = cq.cq_decode_workspace_bytes(cq.make_layout(2, 8, 2, 128, 4096), 32)
-    assert bigger > n
+def test_workspace_size_follows_the_kernels_that_will_run():
+    dyn = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    # the headline configuration: one workgroup owns a row, one launch, no scratch to speak of
+    video = cq.make_layout(64, 32, 8, 128, 8192)
+    assert cq.cq_decode_workspace_bytes(video, 512, dyn) == 256
+    assert cq.cq_decode_workspace_bytes(video, 512, None) == 256
+    # the long-context configuration: rows split into chunks -> extrema + partials, far less than
+    # one float per logit
+    long_ctx = cq.make_layout(8, 48, 8, 128, 65536)
+    n = cq.cq_decode_workspace_bytes(long_ctx, 1024, dyn)
+    assert n % 256 == 0 and 8 * 48 * 2 * (128 + 2) * 4 <= n < 8 * 48 * 65536 * 4 // 8
+    # shape-agnostic kernels (a head dimension the tuned ones do not take): one fp32 logit per
+    # (batch, query head, token) and the partials
+    lay = cq.make_layout(2, 8, 2, 64, 1024, v_group=64)
+    n = cq.cq_decode_workspace_bytes(lay, 32, dyn)
+    assert n % 256 == 0 and n >= 2 * 8 * (1024 + 32) * 4
+    assert cq.cq_decode_workspace_bytes(cq.make_layout(2, 8, 2, 64, 4096, v_group=64), 32, dyn) > n
+    # invalid layout, tail length or calibration mode
+    assert cq.cq_decode_workspace_bytes(cq.make_layout(2, 8, 2, 100, 1024), 32, dyn) == 0
+    assert cq.cq_decode_workspace_bytes(video, -1, dyn) == 0
+    assert cq.cq_decode_workspace_bytes(video, 512, cq.make_calib(9)) == 0
 
 
-def test_kernel_path_switch():
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_GENERIC)
-    assert cq.cq_set_kernel_path(prev) == cq.CQ_PATH_GENERIC
+def test_switches_are_per_thread_and_the_size_query_follows_them():
+    import threading
+    video = cq.make_layout(64, 32, 8, 128, 8192)
+    dyn = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    assert cq.cq_bench_set_kernel_path(cq.CQ_PATH_GENERIC) == cq.CQ_PATH_AUTO
+    try:
+        assert cq.cq_decode_workspace_bytes(video, 512, dyn) >= 64 * 32 * (8192 + 512) * 4
+        seen = {}
+
+        def other():        # another thread still sees the defaults, and its changes stay its own
+            seen["path"] = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
+            seen["chunks"] = cq.cq_bench_set_decode_chunks(5)
+            seen["bytes"] = cq.cq_decode_workspace_bytes(video, 512, dyn)
+
+        t = threading.Thread(target=other)
+        t.start()
+        t.join()
+        assert seen["path"] == cq.CQ_PATH_AUTO and seen["chunks"] == 0
+        assert seen["bytes"] > 256          # five chunks per row: partials
+    finally:
+        assert cq.cq_bench_set_kernel_path(cq.CQ_PATH_AUTO) == cq.CQ_PATH_GENERIC
+    assert cq.cq_bench_set_decode_chunks(0) == 0
+    assert cq.cq_decode_workspace_bytes(video, 512, dyn) == 256
     with pytest.raises(cq.CqError):
-        cq.cq_set_kernel_path(42)
+        cq.cq_bench_set_kernel_path(42)
+    with pytest.raises(cq.CqError):
+        cq.cq_bench_set_decode_chunks(-1)
+    # TUNED makes a layout without a tuned kernel an error instead of a fallback
+    cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        assert cq.cq_decode_workspace_bytes(cq.make_layout(2, 8, 2, 64, 1024, v_group=64), 32, dyn) == 0
+        assert _decode(cq.make_layout(2, 8, 2, 64, 256, v_group=64)) == cq.CQ_ERR_UNSUPPORTED
+    finally:
+        cq.cq_bench_set_kernel_path(cq.CQ_PATH_AUTO)
+
+
+def test_devlen_argument_errors():
+    lay = cq.make_layout(2, 8, 2, 128, 256)
+    L = cq.lib()
+    ks, vs = cq.CqQTensor(FAKE, FAKE, FAKE), cq.CqQTensor(FAKE, FAKE, FAKE)
+
+    def dec(n_dev=FAKE, n_max=4, cap=4, ws_bytes=1 << 40):
+        return L.cq_decode_attn_devlen(ctypes.byref(lay), FAKE, ctypes.byref(ks), ctypes.byref(vs),
+                                       FAKE, FAKE, n_dev, n_max, cap, None, 0.0, FAKE, FAKE, ws_bytes, None)
+
+    assert dec(n_dev=None) == cq.CQ_ERR_NULL
+    assert dec(n_dev=FAKE + 2) == cq.CQ_ERR_ALIGN
+    assert dec(n_max=5) == cq.CQ_ERR_SHAPE
+    assert dec(ws_bytes=16) == cq.CQ_ERR_WORKSPACE
+    f = L.cq_append_text_kv_devlen
+    assert f(ctypes.byref(lay), FAKE, FAKE, None, 4, FAKE, FAKE, None) == cq.CQ_ERR_NULL
+    assert f(ctypes.byref(lay), FAKE, FAKE, FAKE + 1, 4, FAKE, FAKE, None) == cq.CQ_ERR_ALIGN
+    assert f(ctypes.byref(lay), FAKE, FAKE, FAKE, 0, FAKE, FAKE, None) == cq.CQ_ERR_SHAPE
+    assert f(ctypes.byref(lay), None, FAKE, FAKE, 4, FAKE, FAKE, None) == cq.CQ_ERR_NULL
 
 
 def test_binding_raises_when_library_is_missing(monkeypatch):

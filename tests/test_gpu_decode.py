@@ -30,9 +30,9 @@ def pytest_generate_tests(metafunc):
 def kernel_path(request):
     """Every case runs twice: on the shape-agnostic kernels and on whatever AUTO selects
     (the tuned kernels where the layout allows)."""
-    prev = cq.cq_set_kernel_path({"generic": cq.CQ_PATH_GENERIC, "auto": cq.CQ_PATH_AUTO}[request.param])
+    prev = cq.cq_bench_set_kernel_path({"generic": cq.CQ_PATH_GENERIC, "auto": cq.CQ_PATH_AUTO}[request.param])
     yield request.param
-    cq.cq_set_kernel_path(prev)
+    cq.cq_bench_set_kernel_path(prev)
 
 
 class Case:
@@ -178,12 +178,12 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path):
     w4 = synth.WORKLOADS[4].replace(batch=1, n_kv_heads=1, n_q_heads=6, n_vis=16384, n_text=1024)
     cases.append(Case(w4, H.layout_of(w4, 1)))
     cases.append(Case(w4, H.layout_of(w4, 2)))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for c in cases:
             c.check()
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 # the layouts that bench.py times on configs[2]: (bits, key group, value axis, value group); a group
@@ -205,13 +205,13 @@ def test_full_size_benchmark_config_on_sampled_rows(kernel_path, bits, k_group, 
     lay = H.layout_of(w, bits, k_group, v_group, 0, v_axis)
     x = synth.make_inputs(w, "cuda")
     k_dev, v_dev = cq.cq_quantize_kv(lay, x["k"], x["v"])
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         out = cq.cq_decode_attn(lay, x["q"], k_dev, v_dev, x["k_text"], x["v_text"], w.n_text,
                                 cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0))
         torch.cuda.synchronize()
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
     g = w.n_q_heads // w.n_kv_heads
     rng = np.random.default_rng(5)
     rows = {(0, 0), (w.batch - 1, w.n_kv_heads - 1)}
@@ -239,23 +239,23 @@ def test_full_size_benchmark_config_on_sampled_rows(kernel_path, bits, k_group, 
 
 @pytest.mark.tuned_only
 @pytest.mark.parametrize("chunks", [1, 2, 5])
-def test_split_rows_agree_with_whole_rows(kernel_path, chunks, monkeypatch):
+def test_split_rows_agree_with_whole_rows(kernel_path, chunks, decode_chunks):
     """The tuned kernel on whole rows (one launch) and on rows split into chunks (extrema pass,
     partial pass, combine) must both match the oracle; g = 4 and g = 6 (two blocks of heads)."""
-    monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
+    decode_chunks(chunks)
     prev = None
     cases = []
     for w in (synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200),
               synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=2560, n_text=130)):
         cases.append(Case(w, H.layout_of(w)))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for c in cases:
             c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
             c.check(cq.CQ_CALIB_NONE)
             c.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
@@ -268,19 +268,19 @@ def test_tuned_channelwise_values(kernel_path, bits, kg, vg):
     for w in (synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=2304, n_text=200),
               synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=1280, n_text=70)):
         cases.append(Case(w, H.layout_of(w, bits, kg, vg, 0, 0)))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for c in cases:
             c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
             c.check(cq.CQ_CALIB_NONE)
             c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, n_text=0)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
 @pytest.mark.parametrize("bits,v_whole", [(1, False), (2, False), (4, False), (8, False), (1, True), (2, True)])
-def test_tuned_whole_sequence_statistics(kernel_path, bits, v_whole, monkeypatch):
+def test_tuned_whole_sequence_statistics(kernel_path, bits, v_whole, decode_chunks):
     """Sec. 3.1 as printed: one (scale, min) pair per channel over ALL visual tokens, for keys and
     (v_whole) for values too, on the tuned kernels; whole rows and rows split into chunks."""
     cases = []
@@ -288,34 +288,34 @@ def test_tuned_whole_sequence_statistics(kernel_path, bits, v_whole, monkeypatch
               synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=1280, n_text=70)):
         lay = H.layout_of(w, bits, w.n_vis, w.n_vis if v_whole else 128, 0, 0 if v_whole else 1)
         cases.append(Case(w, lay))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for c in cases:
             c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
             c.check(cq.CQ_CALIB_NONE, n_text=0)
-        monkeypatch.setenv("CQ_DECODE_CHUNKS", "3")
+        decode_chunks(3)
         for c in cases:
             c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
             c.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
 @pytest.mark.parametrize("chunks", [2, 3])
-def test_tuned_channelwise_values_on_split_rows(kernel_path, chunks, monkeypatch):
-    monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
+def test_tuned_channelwise_values_on_split_rows(kernel_path, chunks, decode_chunks):
+    decode_chunks(chunks)
     cases = []
     for kg, vg in ((128, 128), (32, 128), (64, 64)):
         w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200)
         cases.append(Case(w, H.layout_of(w, 1, kg, vg, 0, 0)))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for c in cases:
             c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
             c.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
@@ -323,24 +323,24 @@ def test_full_length_row_with_channelwise_values(kernel_path):
     """configs[2]-length rows (8192 + 512 tokens) with channel-wise values, tuned kernels."""
     w = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8)
     c = Case(w, H.layout_of(w, 1, 128, 128, 0, 0))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
 @pytest.mark.parametrize("chunks", [1, 3])
-def test_decode_replayed_from_a_hip_graph(kernel_path, chunks, monkeypatch):
+def test_decode_replayed_from_a_hip_graph(kernel_path, chunks, decode_chunks):
     """cq_decode_attn allocates nothing and blocks on nothing, so a serving loop can record it
     into a HIP graph: every replay, with eager work and synchronisations in between, must
     reproduce the eager result bit for bit (whole rows and split rows)."""
-    monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
+    decode_chunks(chunks)
     w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200)
     c = Case(w, H.layout_of(w))
     calib = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
-    ws = torch.empty(cq.cq_decode_workspace_bytes(c.lay, w.n_text), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(cq.cq_decode_workspace_bytes(c.lay, w.n_text, calib), dtype=torch.uint8, device="cuda")
     qs = [c.x["q"], (c.x["q"] * 0.5).contiguous(), (-c.x["q"]).contiguous()]
     eager = []
     for q in qs:
@@ -383,13 +383,13 @@ def test_full_size_long_context_config_on_sampled_rows(kernel_path, bits):
     lay = H.layout_of(w, bits)
     x = synth.make_inputs(w, "cuda")
     k_dev, v_dev = cq.cq_quantize_kv(lay, x["k"], x["v"])
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         out = cq.cq_decode_attn(lay, x["q"], k_dev, v_dev, x["k_text"], x["v_text"], w.n_text,
                                 cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0))
         torch.cuda.synchronize()
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
     g = w.n_q_heads // w.n_kv_heads
     for b, h in ((0, 0), (w.batch - 1, w.n_kv_heads - 1), (3, 5)):
         kq = O.quantize_tensor(x["k"][b:b + 1, h:h + 1].cpu().numpy(), bits, O.AXIS_CHANNEL, 128)
@@ -443,6 +443,80 @@ def test_decoding_several_steps_with_a_growing_text_tail(kernel_path):
         assert torch.equal(k_dev.cpu(), k_tail) and torch.equal(v_dev.cpu(), v_tail)
 
 
+@pytest.mark.parametrize("chunks", [0, 3])
+def test_growing_step_recorded_once_and_replayed(kernel_path, chunks, decode_chunks):
+    """Sec. 2.1: every decode step appends the new token's key and value to the cache and attends
+    to all of it.  With the tail length in device memory the step (cq_append_text_kv_devlen, then
+    cq_decode_attn_devlen) is recorded ONCE into a HIP graph and replayed eight times while the
+    tail grows, with eager work and synchronisations between the replays; every replay is checked
+    against the oracle on the tail as it then stands.  Whole rows and rows split into chunks."""
+    if chunks and kernel_path == "generic":
+        pytest.skip("the chunk override only concerns the tuned kernels")
+    decode_chunks(chunks)
+    w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1280, n_text=59)
+    c = Case(w, H.layout_of(w))
+    cap, steps = 70, 8
+    B, Hkv, d = w.batch, w.n_kv_heads, w.head_dim
+    gen = torch.Generator().manual_seed(91)
+    k_tail = torch.zeros(B, Hkv, cap, d, dtype=torch.float16)
+    v_tail = torch.zeros(B, Hkv, cap, d, dtype=torch.float16)
+    k_tail[:, :, :w.n_text] = c.x_cpu["k_text"]
+    v_tail[:, :, :w.n_text] = c.x_cpu["v_text"]
+    k_dev, v_dev = k_tail.cuda(), v_tail.cuda()
+    calib = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    n_max = w.n_text + steps
+    ws = torch.empty(cq.cq_decode_workspace_bytes(c.lay, n_max, calib), dtype=torch.uint8, device="cuda")
+    n_dev = torch.tensor([w.n_text], dtype=torch.int32, device="cuda")
+    q_buf = torch.zeros(B, w.n_q_heads, d, dtype=torch.float16, device="cuda")
+    k_new = torch.zeros(B, Hkv, 1, d, dtype=torch.float16, device="cuda")
+    v_new = torch.zeros(B, Hkv, 1, d, dtype=torch.float16, device="cuda")
+    out = torch.zeros_like(q_buf)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):       # warm-up on the capture stream (decode only: the tail stays)
+        cq.cq_decode_attn_devlen(c.lay, q_buf, c.k_dev, c.v_dev, k_dev, v_dev, n_dev, n_max, calib,
+                                 0.0, out, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cq.cq_append_text_kv_devlen(c.lay, k_dev, v_dev, n_dev, k_new, v_new)
+        cq.cq_decode_attn_devlen(c.lay, q_buf, c.k_dev, c.v_dev, k_dev, v_dev, n_dev, n_max, calib,
+                                 0.0, out, ws)
+    torch.cuda.synchronize()
+    assert int(n_dev.item()) == w.n_text, "recording a graph must not run it"
+    n_text = w.n_text
+    for step in range(steps):
+        q = torch.randn(B, w.n_q_heads, d, generator=gen).to(torch.float16)
+        kn = torch.randn(B, Hkv, 1, d, generator=gen).to(torch.float16)
+        vn = torch.randn(B, Hkv, 1, d, generator=gen).to(torch.float16)
+        q_buf.copy_(q)                  # eager work between the replays
+        k_new.copy_(kn)
+        v_new.copy_(vn)
+        out.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        k_tail[:, :, n_text] = kn[:, :, 0]
+        v_tail[:, :, n_text] = vn[:, :, 0]
+        n_text += 1
+        assert int(n_dev.item()) == n_text
+        assert torch.equal(k_dev.cpu(), k_tail) and torch.equal(v_dev.cpu(), v_tail)
+        ref = O.decode_attn(q.numpy(), c.kq, c.vq, k_tail.numpy(), v_tail.numpy(), n_text,
+                            O.CALIB_DYNAMIC, 1.0, 2.0)
+        got = out.cpu().numpy().astype(np.float64)
+        err = O.rel_l2(got, ref)
+        assert err <= H.REL_L2_TOL, "replay %d (tail of %d): rel L2 %.3e" % (step, n_text, err)
+    # a full tail: the append leaves tails and counter alone, and the decode still attends to cap tokens
+    n_dev.fill_(cap)
+    before = (k_dev.clone(), v_dev.clone())
+    cq.cq_append_text_kv_devlen(c.lay, k_dev, v_dev, n_dev, k_new, v_new)
+    torch.cuda.synchronize()
+    assert int(n_dev.item()) == cap
+    assert torch.equal(k_dev, before[0]) and torch.equal(v_dev, before[1])
+
+
 @pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("kg", [32, 64, 128])
@@ -453,31 +527,31 @@ def test_tuned_wide_codes(kernel_path, bits, kg):
     for w in (synth.WORKLOADS[2].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1536, n_text=200),
               synth.WORKLOADS[4].replace(batch=1, n_kv_heads=2, n_q_heads=12, n_vis=1280, n_text=70)):
         cases.append(Case(w, H.layout_of(w, bits, kg, 128)))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for c in cases:
             c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
             c.check(cq.CQ_CALIB_NONE)
             c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, n_text=0)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [4, 8])
-def test_tuned_wide_codes_on_split_and_full_length_rows(kernel_path, bits, monkeypatch):
+def test_tuned_wide_codes_on_split_and_full_length_rows(kernel_path, bits, decode_chunks):
     w_full = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8)
     full = Case(w_full, H.layout_of(w_full, bits))
     w = synth.WORKLOADS[1].replace(batch=2, n_kv_heads=2, n_q_heads=8, n_vis=1920, n_text=200)
     split = Case(w, H.layout_of(w, bits))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         full.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
-        monkeypatch.setenv("CQ_DECODE_CHUNKS", "3")
+        decode_chunks(3)
         split.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
         split.check(cq.CQ_CALIB_FIXED, 1.0, 2.0, gamma=-30.0, delta=30.0)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
@@ -492,12 +566,12 @@ def test_text_only_rows_on_the_tuned_kernel(kernel_path, n_text, n_q_heads):
     w = synth.WORKLOADS[2].replace(batch=2, n_kv_heads=1, n_q_heads=n_q_heads, n_vis=0,
                                    n_text=n_text, seed=7300 + n_text)
     c = Case(w, H.layout_of(w))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         c.check(cq.CQ_CALIB_NONE, tol=3e-4)
         c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0, tol=3e-4)      # no visual tokens: nothing to calibrate
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
@@ -509,20 +583,20 @@ def test_long_whole_rows(kernel_path, bits, n_vis, n_text):
     w = synth.WORKLOADS[2].replace(batch=1, n_kv_heads=2, n_q_heads=8, n_vis=n_vis, n_text=n_text,
                                    seed=7100 + bits)
     c = Case(w, H.layout_of(w, bits))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
         c.check(cq.CQ_CALIB_NONE)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
-def test_random_layouts_on_the_tuned_kernels(kernel_path, monkeypatch):
+def test_random_layouts_on_the_tuned_kernels(kernel_path, decode_chunks):
     """Seeded sweep over the layouts the tuned kernels accept: code width, group sizes, value
     axis, heads per KV head (1..8), ragged text tails, forced row splits, calibration modes."""
     rng = np.random.default_rng(2024)
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for trial in range(24):
             bits = int(rng.choice([1, 2, 4, 8]))
@@ -541,7 +615,7 @@ def test_random_layouts_on_the_tuned_kernels(kernel_path, monkeypatch):
             unit = max(128, min(vg, 128) if vch else 64, min(kg, 128))
             if n_vis // unit < chunks:
                 chunks = 1
-            monkeypatch.setenv("CQ_DECODE_CHUNKS", str(chunks))
+            decode_chunks(chunks)
             w = synth.WORKLOADS[int(rng.choice([1, 4]))].replace(
                 batch=int(rng.integers(1, 3)), n_kv_heads=hkv, n_q_heads=hkv * g, n_vis=n_vis,
                 n_text=n_text, seed=5000 + trial)
@@ -554,4 +628,4 @@ def test_random_layouts_on_the_tuned_kernels(kernel_path, monkeypatch):
                                      "chunks %d mode %d): %s" % (trial, bits, kg, vg, vch, g, hkv, n_vis,
                                                                  n_text, chunks, mode, e))
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)

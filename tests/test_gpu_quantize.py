@@ -23,9 +23,9 @@ def pytest_generate_tests(metafunc):
 @pytest.fixture(autouse=True, scope="module")
 def kernel_path(request):
     """Every case runs on the shape-agnostic kernels and on whatever AUTO selects."""
-    prev = cq.cq_set_kernel_path({"generic": cq.CQ_PATH_GENERIC, "auto": cq.CQ_PATH_AUTO}[request.param])
+    prev = cq.cq_bench_set_kernel_path({"generic": cq.CQ_PATH_GENERIC, "auto": cq.CQ_PATH_AUTO}[request.param])
     yield request.param
-    cq.cq_set_kernel_path(prev)
+    cq.cq_bench_set_kernel_path(prev)
 
 
 def _run(w, lay, x_cpu=None, what=""):
@@ -132,7 +132,7 @@ def test_runs_on_a_side_stream():
 def test_tuned_path_takes_the_benchmark_layouts(kernel_path, bits, group):
     """head_dim 128, b in {1,2}, groups 32/64/128 must run on the tuned kernels (no silent
     fallback) and stay bit-exact, including exact ties and heavy-tailed outliers."""
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         w = synth.WORKLOADS[4].replace(batch=2, n_kv_heads=2, n_q_heads=2, n_vis=1024)
         x = synth.make_inputs(w, "cpu", parts=("k", "v"))
@@ -144,7 +144,7 @@ def test_tuned_path_takes_the_benchmark_layouts(kernel_path, bits, group):
         x["v"][1, 1, 10, :] = torch.tensor([-0.0, 0.0] * 64)
         _run(w, H.layout_of(w, bits, group, group), x, what="tuned b=%d G=%d" % (bits, group))
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
@@ -154,7 +154,7 @@ def test_tuned_whole_sequence_statistics(kernel_path, bits, n_vis):
     """Sec. 3.1 as printed (one pair per channel over all tokens, keys and values) on the tuned
     kernels: extrema pass + tile pass, with exact ties, a constant channel, signed zeros and rows
     whose extreme elements sit in the first and in the last tile."""
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         w = synth.WORKLOADS[4].replace(batch=2, n_kv_heads=2, n_q_heads=2, n_vis=n_vis)
         x = synth.make_inputs(w, "cpu", parts=("k", "v"))
@@ -169,7 +169,7 @@ def test_tuned_whole_sequence_statistics(kernel_path, bits, n_vis):
         x["v"][0, 0, n_vis // 2, 64] = 60000.0
         _run(w, H.layout_of(w, bits, n_vis, n_vis, 0, 0), x, what="whole sequence b=%d" % bits)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
@@ -182,12 +182,12 @@ def test_full_size_quantizer_config_on_sampled_rows(kernel_path, bits, group):
     w = synth.WORKLOADS[3]
     lay = H.layout_of(w, bits, group, group)
     x = synth.make_inputs(w, "cuda", parts=("k", "v"))
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         k_out, v_out = cq.cq_quantize_kv(lay, x["k"], x["v"])
         torch.cuda.synchronize()
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
     rng = np.random.default_rng(11)
     rows = {(0, 0), (w.batch - 1, w.n_kv_heads - 1)}
     while len(rows) < 5:
@@ -215,13 +215,13 @@ def test_wide_codes_round_exact_ties_to_even_on_the_tuned_path(kernel_path, bits
     x["k"][0, 0, :, 8] = -ties
     for t in range(0, 512, 37):
         x["v"][0, 0, t, :] = ties[:128] if bits == 4 else ties[t % 64:t % 64 + 128]
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for group in (32, 128):
             _run(w, H.layout_of(w, bits, group, group), x, what="ties b=%d G=%d" % (bits, group))
             _run(w, H.layout_of(w, bits, group, group, 1, 0), x, what="ties swapped b=%d" % bits)
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
@@ -229,7 +229,7 @@ def test_random_layouts_on_the_tuned_quantizer(kernel_path):
     """Seeded sweep over what the tuned quantizer accepts: code width, group size, either axis for
     keys and values, row counts and lengths; heavy-tailed and outlier inputs; bit-exact."""
     rng = np.random.default_rng(99)
-    prev = cq.cq_set_kernel_path(cq.CQ_PATH_TUNED)
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
     try:
         for trial in range(20):
             bits = int(rng.choice([1, 2, 4, 8]))
@@ -242,7 +242,7 @@ def test_random_layouts_on_the_tuned_quantizer(kernel_path):
             _run(w, H.layout_of(w, bits, kg, vg, ka, va),
                  what="trial %d b=%d kg=%d vg=%d axes=%d%d" % (trial, bits, kg, vg, ka, va))
     finally:
-        cq.cq_set_kernel_path(prev)
+        cq.cq_bench_set_kernel_path(prev)
 
 
 @pytest.mark.tuned_only
