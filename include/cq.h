@@ -168,6 +168,28 @@ int cq_append_text_kv(const cq_layout_t *layout, void *k_text_f16, void *v_text_
                       const void *v_new_f16, void *stream);
 
 /*
+ * cq_decode_attn for callers that cannot allocate or hand over scratch memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * (bit for bit) and errors as cq_decode_attn, without the workspace: whatever scratch the
+ * selected kernels need (chunk extrema and online-softmax partials of split rows, logits of the
+ * shape-agnostic kernels) lives in an array of CQ_NOALLOC_SCRATCH_BYTES inside the library's
+ * device image, one copy per GPU, held until the process ends.  The call allocates and frees
+ * nothing; the first call on a device looks the array's address up once (not under capture).
+ * A shape that needs more scratch than the array holds (compare
+ * cq_decode_workspace_bytes(layout, n_text, calib) with CQ_NOALLOC_SCRATCH_BYTES) returns
+ * CQ_ERR_WORKSPACE and launches nothing: use cq_decode_attn with a workspace for it.
+ * Every call on a GPU shares that GPU's array and nothing in it needs clearing between calls
+ * (each call writes what it reads), but two calls that overlap in time on one GPU - different
+ * streams, or different threads - race on it: serialise them, or give them workspaces.
+ */
+#define CQ_NOALLOC_SCRATCH_BYTES (8u << 20)
+int cq_decode_attn_noalloc(const cq_layout_t *layout, const void *q_f16, const cq_qtensor_t *k,
+                           const cq_qtensor_t *v, const void *k_text_f16,
+                           const void *v_text_f16, int32_t n_text, int32_t n_text_cap,
+                           const cq_calib_t *calib, float softmax_scale, void *out_f16,
+                           void *stream);
+
+/*
  * The same two steps with the tail length held in DEVICE memory, so that one decode step
  * (append the new token, then attend) can be recorded once into a HIP graph and replayed while
  * the tail grows (Sec. 2.1: every decode step appends the new key and value to the cache).

@@ -63,6 +63,9 @@ def lib() -> ctypes.CDLL:
         L.cq_decode_attn.restype = ctypes.c_int
         L.cq_decode_attn.argtypes = [P(CqLayout), V, P(CqQTensor), P(CqQTensor), V, V, I, I,
                                      P(CqCalib), ctypes.c_float, V, V, ctypes.c_size_t, V]
+        L.cq_decode_attn_noalloc.restype = ctypes.c_int
+        L.cq_decode_attn_noalloc.argtypes = [P(CqLayout), V, P(CqQTensor), P(CqQTensor), V, V, I, I,
+                                             P(CqCalib), ctypes.c_float, V, V]
         L.cq_append_text_kv.restype = ctypes.c_int
         L.cq_append_text_kv.argtypes = [P(CqLayout), V, V, I, I, V, V, V]
         L.cq_append_text_kv_devlen.restype = ctypes.c_int
@@ -225,6 +228,35 @@ def cq_decode_attn(layout: CqLayout, q: torch.Tensor, k: Optional[QTensor], v: O
         _ptr(k_text), _ptr(v_text), int(n_text), int(n_text_cap),
         ctypes.byref(calib) if calib is not None else None, float(softmax_scale),
         _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(q)))
+    return out
+
+
+CQ_NOALLOC_SCRATCH_BYTES = 8 << 20
+
+
+def cq_decode_attn_noalloc(layout: CqLayout, q: torch.Tensor, k: Optional[QTensor],
+                           v: Optional[QTensor], k_text: Optional[torch.Tensor],
+                           v_text: Optional[torch.Tensor], n_text: int,
+                           calib: Optional[CqCalib] = None, softmax_scale: float = 0.0,
+                           out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """cq_decode_attn without a workspace: the library's own per-GPU scratch array serves.  `out`
+    should be given by a caller that must not allocate (it is allocated here otherwise)."""
+    if out is None:
+        out = torch.empty_like(q)
+    n_text_cap = _check_decode_tensors(layout, q, k_text, v_text, out)
+    assert 0 <= n_text <= n_text_cap
+    if layout.n_vis > 0:
+        _check_qtensor(layout, k, layout.k_axis, layout.k_group, "key")
+        _check_qtensor(layout, v, layout.v_axis, layout.v_group, "value")
+    ks = k.c_struct() if k is not None else None
+    vs = v.c_struct() if v is not None else None
+    _check(lib().cq_decode_attn_noalloc(
+        ctypes.byref(layout), _ptr(q),
+        ctypes.byref(ks) if ks is not None else None,
+        ctypes.byref(vs) if vs is not None else None,
+        _ptr(k_text), _ptr(v_text), int(n_text), int(n_text_cap),
+        ctypes.byref(calib) if calib is not None else None, float(softmax_scale),
+        _ptr(out), _stream(q)))
     return out
 
 

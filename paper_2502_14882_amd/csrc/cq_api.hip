@@ -1,5 +1,6 @@
 // Host side of libcq: argument validation, kernel-path selection, status strings.
 // Every check here runs before the first HIP call, so a rejected call launches nothing.
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -218,6 +219,32 @@ int launch_decode(const DecodeCall& call, const void* q_f16, const cq_qtensor_t*
   return CQ_OK;
 }
 
+// Scratch of the allocation-free entry point: part of the library's device image, so every GPU the
+// library runs on holds its own copy at its own address until the process ends.  On the host
+// this name is only a handle for hipGetSymbolAddress, never an address: kernels and copies get
+// the pointer that noalloc_scratch() returns.
+static __device__ __align__(256) unsigned char scratch[CQ_NOALLOC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up once per device.
+int noalloc_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(CQ_ERR_HIP, "device index %d is out of range", dev);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255u) != 0)
+      return fail(CQ_ERR_HIP, "the scratch array has no 256-byte aligned device address");
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // same value from every thread
+  }
+  *out = p;
+  return CQ_OK;
+}
+
 int check_workspace(const void* workspace, size_t workspace_bytes, size_t need) {
   if (!workspace) return fail(CQ_ERR_WORKSPACE, "workspace is NULL");
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
@@ -324,6 +351,24 @@ int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* 
   if (rc != CQ_OK) return rc;
   if ((rc = check_workspace(workspace, workspace_bytes, call.ws_bytes)) != CQ_OK) return rc;
   return launch_decode(call, q_f16, k, v, k_text_f16, v_text_f16, nullptr, out_f16, workspace, stream);
+}
+
+int cq_decode_attn_noalloc(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* k,
+                           const cq_qtensor_t* v, const void* k_text_f16, const void* v_text_f16,
+                           int32_t n_text, int32_t n_text_cap, const cq_calib_t* calib,
+                           float softmax_scale, void* out_f16, void* stream) {
+  DecodeCall call;
+  int rc = check_decode(L, q_f16, k, v, k_text_f16, v_text_f16, n_text, n_text_cap, false, calib,
+                        softmax_scale, out_f16, &call);
+  if (rc != CQ_OK) return rc;
+  if (call.ws_bytes > (size_t)CQ_NOALLOC_SCRATCH_BYTES)
+    return fail(CQ_ERR_WORKSPACE,
+                "this shape needs %zu bytes of scratch, the allocation-free entry point holds %zu: "
+                "call cq_decode_attn with a workspace", call.ws_bytes,
+                (size_t)CQ_NOALLOC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  if ((rc = noalloc_scratch(&ws)) != CQ_OK) return rc;
+  return launch_decode(call, q_f16, k, v, k_text_f16, v_text_f16, nullptr, out_f16, ws, stream);
 }
 
 int cq_decode_attn_devlen(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* k,

@@ -22,7 +22,7 @@ def _declared_functions(header):
 # the product ABI: the two operations of the hot path with their size query, the steps either
 # side of them, status reporting, and the entry point for callers that cannot allocate
 PRODUCT_ABI = ["cq_append_text_kv", "cq_append_text_kv_devlen", "cq_decode_attn",
-               "cq_decode_attn_devlen", "cq_decode_workspace_bytes",
+               "cq_decode_attn_devlen", "cq_decode_attn_noalloc", "cq_decode_workspace_bytes",
                "cq_last_error", "cq_quantize_kv", "cq_status_string", "cq_tau_search",
                "cq_tau_search_workspace_bytes", "cq_version"]
 BENCH_ABI = ["cq_bench_set_decode_chunks", "cq_bench_set_kernel_path", "cq_bench_stream_copy",
@@ -235,6 +235,33 @@ def test_switches_are_per_thread_and_the_size_query_follows_them():
         assert _decode(cq.make_layout(2, 8, 2, 64, 256, v_group=64)) == cq.CQ_ERR_UNSUPPORTED
     finally:
         cq.cq_bench_set_kernel_path(cq.CQ_PATH_AUTO)
+
+
+def test_noalloc_entry_point_rejects_what_its_scratch_cannot_hold():
+    """The allocation-free decode checks its arguments like cq_decode_attn and turns a shape whose
+    scratch exceeds the library's array into CQ_ERR_WORKSPACE, all before any HIP call."""
+    L = cq.lib()
+    ks, vs = cq.CqQTensor(FAKE, FAKE, FAKE), cq.CqQTensor(FAKE, FAKE, FAKE)
+
+    def call(lay, q=FAKE, n_text=4, cap=4, calib=None):
+        return L.cq_decode_attn_noalloc(ctypes.byref(lay), q, ctypes.byref(ks), ctypes.byref(vs), FAKE,
+                                        FAKE, n_text, cap, ctypes.byref(calib) if calib else None,
+                                        0.0, FAKE, None)
+
+    dyn = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    # shape-agnostic kernels (head_dim 64) with 16 MB of logits: more than the array holds
+    big = cq.make_layout(8, 32, 8, 64, 16384, v_group=64)
+    assert cq.cq_decode_workspace_bytes(big, 4, dyn) > cq.CQ_NOALLOC_SCRATCH_BYTES
+    assert call(big, calib=dyn) == cq.CQ_ERR_WORKSPACE
+    assert b"allocation-free" in L.cq_last_error()
+    # the long-context configuration fits (split rows: extrema and partials only)
+    assert cq.cq_decode_workspace_bytes(cq.make_layout(8, 48, 8, 128, 65536), 1024, dyn) \
+        <= cq.CQ_NOALLOC_SCRATCH_BYTES
+    lay = cq.make_layout(2, 8, 2, 128, 256)
+    assert call(lay, q=None) == cq.CQ_ERR_NULL
+    assert call(lay, q=FAKE + 2) == cq.CQ_ERR_ALIGN
+    assert call(lay, n_text=5) == cq.CQ_ERR_SHAPE
+    assert call(lay, calib=cq.make_calib(9)) == cq.CQ_ERR_UNSUPPORTED
 
 
 def test_devlen_argument_errors():
