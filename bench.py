@@ -187,8 +187,8 @@ def main() -> int:
                 quant_ms.append(e0.elapsed_time(e1))
         sets.append(dict(q=x["q"], k=k_q, v=v_q, k_text=x["k_text"], v_text=x["v_text"],
                          out=torch.empty_like(x["q"])))
-        if i == 0:
-            sample0 = {n: x[n][:1].cpu() for n in ("k", "v", "q", "k_text", "v_text")}
+        if i == 0 and not args.no_cpu_baseline:      # the oracle's inputs: set 0, whole, on the host
+            host0 = {n: x[n].cpu().numpy() for n in ("k", "v", "q", "k_text", "v_text")}
         del x
     ws = torch.empty(cq.cq_decode_workspace_bytes(lay, w.n_text, calib), dtype=torch.uint8, device=dev)
 
@@ -453,33 +453,36 @@ def main() -> int:
     }
 
     if not args.no_cpu_baseline:
-        # the oracle as it stands, on one batch item of the same workload (sample of the call)
+        # The oracle as it stands (its C++ form: dequantize, then plain fp64 loops, rows spread over
+        # the host's threads with OpenMP) on the WHOLE call of input set 0: it quantizes the fp16
+        # cache itself (untimed here, reported separately), then the decode step is timed.
         from oracle import cq_oracle as O
-        kq = O.quantize_tensor(sample0["k"].numpy(), args.bits, O.AXIS_CHANNEL, k_group)
-        vq = O.quantize_tensor(sample0["v"].numpy(), args.bits,
-                               O.AXIS_CHANNEL if args.v_axis == "channel" else O.AXIS_TOKEN, v_group)
+        from oracle import cq_oracle_native as ON
+        v_ax = O.AXIS_CHANNEL if args.v_axis == "channel" else O.AXIS_TOKEN
+        c0 = time.perf_counter()
+        kq = ON.quantize_tensor(host0["k"], args.bits, O.AXIS_CHANNEL, k_group)
+        vq = ON.quantize_tensor(host0["v"], args.bits, v_ax, v_group)
+        t_quant = time.perf_counter() - c0
         n_rep, t_used = 0, 0.0
-        while t_used < 12.0 and n_rep < 400:
+        while t_used < 10.0 and n_rep < 20:
             c0 = time.perf_counter()
-            ref = O.decode_attn(sample0["q"].numpy(), kq, vq, sample0["k_text"].numpy(),
-                                sample0["v_text"].numpy(), w.n_text, O.CALIB_DYNAMIC, 1.0, 2.0)
+            ref = ON.decode_attn(host0["q"], kq, vq, host0["k_text"], host0["v_text"], w.n_text,
+                                 O.CALIB_DYNAMIC, 1.0, 2.0)
             t_used += time.perf_counter() - c0
             n_rep += 1
-        out0 = sets[0]["out"]
         step(0)
         torch.cuda.synchronize()
-        err = O.rel_l2(out0[:1].cpu().numpy().astype(np.float64), ref)
-        try:
-            import threadpoolctl
-            cores = max([p["num_threads"] for p in threadpoolctl.threadpool_info()] or [1])
-        except Exception:
-            cores = 1
+        got = sets[0]["out"].cpu().numpy().astype(np.float64)
         result["cpu_baseline"] = {
-            "value": (w.n_vis + w.n_text) * n_rep / t_used, "unit": "KV tokens/s",
-            "cores": cores, "kind": "oracle",
-            "sample": "batch item 0 of input set 0 (%d of %d sequences), %d repeats, %.1f s"
-                      % (1, w.batch, n_rep, t_used),
-            "host_cpus": os.cpu_count(), "parity_rel_l2_on_sample": err}
+            "value": kv_tokens * n_rep / t_used, "unit": "KV tokens/s",
+            "cores": ON.max_threads(), "kind": "oracle",
+            "sample": "whole call: all %d sequences of input set 0, %d repeats of the decode step, %.1f s"
+                      % (w.batch, n_rep, t_used),
+            "s_per_call": t_used / n_rep, "oracle_quantize_s": t_quant,
+            "host_cpus": os.cpu_count(),
+            "parity_rel_l2_whole_call": O.rel_l2(got, ref),
+            "parity_worst_row_rel_l2": float((np.linalg.norm(got - ref, axis=-1)
+                                              / np.linalg.norm(ref, axis=-1)).max())}
 
     print(json.dumps(result))
     return 0

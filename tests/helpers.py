@@ -6,7 +6,12 @@ from oracle import cq_oracle as O
 from paper_2502_14882_amd import binding as cq
 from paper_2502_14882_amd import synth
 
-REL_L2_TOL = 2e-3      # fp16 output, fp32 accumulation, against the fp64 oracle
+REL_L2_TOL = 2e-3      # the contract: fp16 output, fp32 accumulation, against the fp64 oracle
+# Regression bar for the layouts the benchmark times (1- and 2-bit codes, channel-wise keys,
+# token-wise values): the measured error is 2.0e-4 .. 2.5e-4, set by the fp16 rounding of the output
+# (2^-11 / sqrt(3) = 2.8e-4 relative per element at worst, less after averaging over binades), so a
+# kernel change that loses accuracy shows here long before it reaches the contract's 2e-3.
+REGRESSION_TOL = 4e-4
 
 
 def layout_of(w: synth.Workload, bits=1, k_group=128, v_group=128, k_axis=0, v_axis=1):
@@ -22,6 +27,18 @@ def oracle_quantize(x_cpu: dict, lay):
 
 def words_of(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy().view(np.uint32)
+
+
+def assert_elementwise_close(out, ref, what=""):
+    """|out - ref| <= 2e-3 * max|ref| of the (batch, head) row + one fp16 ulp of the reference
+    element: a single bad channel cannot hide behind the norm of its row."""
+    out, ref = np.asarray(out, np.float64), np.asarray(ref, np.float64)
+    row_max = np.abs(ref).max(axis=-1, keepdims=True)
+    ulp = np.spacing(np.abs(ref).astype(np.float16)).astype(np.float64)
+    excess = np.abs(out - ref) - (REL_L2_TOL * row_max + ulp)
+    worst = np.unravel_index(np.argmax(excess), excess.shape)
+    assert excess.max() <= 0.0, "%s element %s: got %.6g, want %.6g (row max %.3g)" % (
+        what, worst, out[worst], ref[worst], row_max[worst[:-1]][0])
 
 
 def assert_qtensor_equal(gpu, ref, what=""):

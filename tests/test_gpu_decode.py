@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from oracle import cq_oracle as O
+from oracle import cq_oracle_native as ON
 from paper_2502_14882_amd import binding as cq
 from paper_2502_14882_amd import synth
 
@@ -65,6 +66,12 @@ class Case:
         err, worst = O.rel_l2(out, ref), H.row_rel_l2(out, ref)
         assert err <= tol, "rel L2 %.3e (worst row %.3e) > %.1e" % (err, worst, tol)
         assert worst <= 4 * tol, "worst row rel L2 %.3e" % worst
+        H.assert_elementwise_close(out, ref)
+        lay = self.lay
+        if (lay.bits <= 2 and lay.k_axis == cq.CQ_AXIS_CHANNEL and lay.v_axis == cq.CQ_AXIS_TOKEN
+                and lay.v_group == lay.head_dim and out.size >= 1024):
+            assert err <= H.REGRESSION_TOL, "rel L2 %.3e is over the regression bar %.1e" % (
+                err, H.REGRESSION_TOL)
         return err
 
 
@@ -224,10 +231,11 @@ def test_full_size_benchmark_config_on_sampled_rows(kernel_path, bits, k_group, 
         vq = O.quantize_tensor(v_row, bits, v_axis, v_group)
         assert np.array_equal(H.words_of(k_dev.codes[b:b + 1, h:h + 1]), kq["words"])
         assert np.array_equal(H.words_of(v_dev.codes[b:b + 1, h:h + 1]), vq["words"])
-        assert np.array_equal(k_dev.scale[b:b + 1, h:h + 1].cpu().numpy().view(np.uint32),
-                              kq["scale"].view(np.uint32))
-        assert np.array_equal(v_dev.min[b:b + 1, h:h + 1].cpu().numpy().view(np.uint16),
-                              vq["min"].view(np.uint16))
+        for dev_t, ref_t in ((k_dev, kq), (v_dev, vq)):
+            assert np.array_equal(dev_t.scale[b:b + 1, h:h + 1].cpu().numpy().view(np.uint32),
+                                  ref_t["scale"].view(np.uint32))
+            assert np.array_equal(dev_t.min[b:b + 1, h:h + 1].cpu().numpy().view(np.uint16),
+                                  ref_t["min"].view(np.uint16))
         ref = O.decode_attn(x["q"][b:b + 1, h * g:(h + 1) * g].cpu().numpy(), kq, vq,
                             x["k_text"][b:b + 1, h:h + 1].cpu().numpy(),
                             x["v_text"][b:b + 1, h:h + 1].cpu().numpy(), w.n_text,
@@ -235,6 +243,7 @@ def test_full_size_benchmark_config_on_sampled_rows(kernel_path, bits, k_group, 
         got = out[b:b + 1, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)
         err = O.rel_l2(got, ref)
         assert err <= H.REL_L2_TOL, "row (%d,%d): rel L2 %.3e" % (b, h, err)
+        H.assert_elementwise_close(got, ref, "row (%d,%d)" % (b, h))
 
 
 @pytest.mark.tuned_only
@@ -403,6 +412,7 @@ def test_full_size_long_context_config_on_sampled_rows(kernel_path, bits):
         got = out[b:b + 1, h * g:(h + 1) * g].cpu().numpy().astype(np.float64)
         err = O.rel_l2(got, ref)
         assert err <= H.REL_L2_TOL, "row (%d,%d): rel L2 %.3e" % (b, h, err)
+        H.assert_elementwise_close(got, ref, "row (%d,%d)" % (b, h))
 
 
 def test_decoding_several_steps_with_a_growing_text_tail(kernel_path):
@@ -629,3 +639,59 @@ def test_random_layouts_on_the_tuned_kernels(kernel_path, decode_chunks):
                                                                  n_text, chunks, mode, e))
     finally:
         cq.cq_bench_set_kernel_path(prev)
+
+
+def _all_rows_check(w, bits, what):
+    """Whole workload at full size: drawn on the GPU as bench.py does, quantized and decoded by the
+    HIP path through the launches bench.py times, and every (batch, head) row - not a sample -
+    compared with the C++ oracle twin (itself tied to the numpy oracle by CPU tests): packed
+    words, scales and minima bit for bit, attention within the contract, the regression bar and the
+    element-wise bound."""
+    lay = H.layout_of(w, bits)
+    calib = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+    x = synth.make_inputs(w, "cuda")
+    k_dev, v_dev = cq.cq_quantize_kv(lay, x["k"], x["v"])
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        out = cq.cq_decode_attn(lay, x["q"], k_dev, v_dev, x["k_text"], x["v_text"], w.n_text, calib)
+        torch.cuda.synchronize()
+    finally:
+        cq.cq_bench_set_kernel_path(prev)
+    host = {n: x[n].cpu().numpy() for n in ("q", "k_text", "v_text")}
+    refs = {}
+    for name, dev_t, axis, group in (("k", k_dev, O.AXIS_CHANNEL, 128), ("v", v_dev, O.AXIS_TOKEN, 128)):
+        ref_t = ON.quantize_tensor(x[name].cpu().numpy(), bits, axis, group)
+        del x[name]
+        assert np.array_equal(H.words_of(dev_t.codes), ref_t["words"]), "%s %s codes" % (what, name)
+        assert np.array_equal(dev_t.scale.cpu().numpy().view(np.uint32), ref_t["scale"].view(np.uint32))
+        assert np.array_equal(dev_t.min.cpu().numpy().view(np.uint16), ref_t["min"].view(np.uint16))
+        refs[name] = ref_t
+    ref = ON.decode_attn(host["q"], refs["k"], refs["v"], host["k_text"], host["v_text"], w.n_text,
+                         O.CALIB_DYNAMIC, 1.0, 2.0)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    err, worst = O.rel_l2(got, ref), H.row_rel_l2(got, ref)
+    assert err <= H.REGRESSION_TOL, "%s: rel L2 %.3e" % (what, err)
+    assert worst <= H.REL_L2_TOL, "%s: worst (batch, head) row rel L2 %.3e" % (what, worst)
+    H.assert_elementwise_close(got, ref, what)
+
+
+@pytest.mark.tuned_only
+@pytest.mark.parametrize("bits", [1, 2])
+def test_headline_config_every_row_at_full_size(kernel_path, bits):
+    """configs[2] (batch 64, 32 / 8 heads, 8192 + 512 tokens): all 512 (batch, KV head) rows."""
+    _all_rows_check(synth.WORKLOADS[2], bits, "configs[2] b=%d" % bits)
+
+
+@pytest.mark.tuned_only
+@pytest.mark.parametrize("bits", [1, 2])
+def test_long_context_config_every_row_at_full_size(kernel_path, bits):
+    """configs[4] (batch 8, 48 / 8 heads, 65536 + 1024 tokens, heavy-tailed keys): all 64 rows
+    through the split-row launches."""
+    _all_rows_check(synth.WORKLOADS[4], bits, "configs[4] b=%d" % bits)
+
+
+@pytest.mark.tuned_only
+def test_small_layer_config_every_row_at_full_size(kernel_path):
+    """configs[1] (batch 16, 32 / 8 heads, 3328 + 128 tokens): all 128 rows."""
+    _all_rows_check(synth.WORKLOADS[1], 1, "configs[1]")

@@ -189,3 +189,21 @@ def test_synth_shapes_determinism_and_outliers():
     w4 = synth.WORKLOADS[4].replace(batch=1, n_vis=512, n_text=8)
     k4 = synth.make_inputs(w4, "cpu", parts=("k",))["k"]
     assert torch.isfinite(k4).all() and k4.abs().max() > 20
+
+
+def test_rel_l2_by_hand():
+    """The parity metric itself, on numbers worked by hand: a = (3, 4, 0), b = (0, 0, 5) ->
+    ||a - b|| = sqrt(9 + 16 + 25) = sqrt(50), ||b|| = 5 -> sqrt(2); the order of the arguments
+    matters (the second one is the reference); identical tensors give 0; a zero reference does not
+    divide by zero; the shape is ignored (norm over the whole tensor)."""
+    a, b = np.array([3.0, 4.0, 0.0]), np.array([0.0, 0.0, 5.0])
+    assert abs(O.rel_l2(a, b) - 2.0 ** 0.5) < 1e-15
+    assert abs(O.rel_l2(b, np.array([3.0, 4.0, 12.0])) - (9 + 16 + 49) ** 0.5 / 13.0) < 1e-15
+    assert O.rel_l2(b, b) == 0.0
+    assert O.rel_l2(a, np.zeros(3)) == 5.0
+    assert abs(O.rel_l2(a.reshape(3, 1), b.reshape(1, 3).T) - 2.0 ** 0.5) < 1e-15
+    # one element off by 1 % in a tensor of 100 equal elements: 0.01 / sqrt(100)
+    x = np.ones(100)
+    y = x.copy()
+    y[7] = 1.01
+    assert abs(O.rel_l2(y, x) - 1e-3) < 1e-12
