@@ -56,6 +56,9 @@ def main() -> int:
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="how the timed steps are launched: replay of one HIP graph holding all "
                          "of them (a serving loop's way), or one call per step from Python")
+    ap.add_argument("--chunks", type=int, default=0,
+                    help="at least this many chunks per row of the tuned decode (0 = the library's "
+                         "own choice): forces the split-row kernels on rows that one workgroup could own")
     ap.add_argument("--tau-search", action="store_true",
                     help="also run and time the grid search of the calibration parameters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -82,6 +85,8 @@ def main() -> int:
     torch.cuda.set_device(dev)
     cq.cq_bench_set_kernel_path({"auto": cq.CQ_PATH_AUTO, "generic": cq.CQ_PATH_GENERIC,
                            "tuned": cq.CQ_PATH_TUNED}[args.path])
+
+    cq.cq_bench_set_decode_chunks(args.chunks)
 
     w = synth.WORKLOADS[args.config]
     if args.batch:
@@ -375,7 +380,13 @@ def main() -> int:
     except cq.CqError:
         fused = False
     cq.cq_bench_set_kernel_path(prev_path)
-    kernel_name = ("fused_row_kernel<%d> (the call's only launch)" % (min(k_group, 128) // 16) if fused
+    split = fused and ws.numel() > 256          # rows split over workgroups: the scratch says so
+    streamed = split and ws.numel() > w.batch * w.n_q_heads * w.n_vis * 2
+    kernel_name = ("stream_logits_kernel + stream_values_kernel + combine_kernel (all launches of one call)"
+                   if streamed else
+                   "fused_row_kernel, extrema pass + partial pass, + combine_kernel (all launches of one call)"
+                   if split else
+                   "fused_row_kernel<%d> (the call's only launch)" % (min(k_group, 128) // 16) if fused
                    else "scores_kernel + pv_kernel + combine_kernel (all launches of one call)")
     # HBM bytes per launch from hardware counters: NOT measured by this run.  The committed summary
     # of two rocprofv3 --pmc runs of this command holds the figure together with the SHA-256 of the
@@ -421,7 +432,7 @@ def main() -> int:
                    "n_vis": w.n_vis, "n_text": w.n_text, "bits": args.bits,
                    "k_group": k_group, "v_group": v_group, "v_axis": args.v_axis,
                    "calib": "dynamic tau=(1,2)",
-                   "kernel_path": args.path, "input_sets": n_sets},
+                   "kernel_path": args.path, "min_chunks": args.chunks, "input_sets": n_sets},
         "launch": args.launch,
         "timed_region": {"launches_between_events": timed_launches,
                          "note": "the graph of `steps` launches replayed back to back, preceded by "

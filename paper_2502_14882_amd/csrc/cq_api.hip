@@ -129,7 +129,9 @@ struct DecodeCall {
   cq::Calib calib;
   float softmax_scale;
   bool tuned;               // the tuned kernels run (else the shape-agnostic ones)
+  bool streamed;            // tuned, split rows: the streaming kernels with logits kept in scratch
   cq::FusedPlan plan;       // valid when tuned
+  cq::StreamPlan stream;    // valid when streamed
   cq::Workspace generic_ws; // valid when !tuned
   size_t ws_bytes;          // scratch the selected kernels touch
 };
@@ -157,14 +159,26 @@ int check_calib(const cq_calib_t* calib, cq::Calib* c) {
 
 // Kernel selection and scratch size for a valid layout: one plan per call, used by the size query,
 // by the argument check and by the launch.
-int select_kernels(const cq_layout_t* L, int n_text, int n_text_cap, DecodeCall* call) {
+// scratch_limit: the most scratch the caller can offer.  Rows that have to be split run on the
+// streaming kernels, which keep the raw logits in scratch (2 bytes per query head and visual
+// token); when that does not fit the limit they run as chunks of the fused kernel, which form the
+// logits twice and keep only extrema and partials.
+int select_kernels(const cq_layout_t* L, int n_text, int n_text_cap, size_t scratch_limit,
+                   DecodeCall* call) {
   call->shape = make_shape(L, n_text, n_text_cap);
   call->plan = cq::make_fused_plan(call->shape, g_decode_chunks);
   if (g_kernel_path == CQ_PATH_TUNED && !call->plan.ok)
     return fail(CQ_ERR_UNSUPPORTED, "no tuned decode kernel for this layout");
   call->tuned = g_kernel_path != CQ_PATH_GENERIC && call->plan.ok;
+  call->streamed = false;
+  if (call->tuned && (call->plan.n_chunks > 1 || call->plan.nhb > 1)) {
+    call->stream = cq::make_stream_plan(call->shape, g_decode_chunks);
+    call->streamed = call->stream.ok && call->stream.ws_bytes <= scratch_limit;
+  }
   call->generic_ws = cq::workspace_layout(L->batch, L->n_q_heads, L->head_dim, L->n_vis, n_text);
-  call->ws_bytes = call->tuned ? call->plan.ws_bytes : call->generic_ws.total_bytes;
+  call->ws_bytes = call->streamed ? call->stream.ws_bytes
+                   : call->tuned  ? call->plan.ws_bytes
+                                  : call->generic_ws.total_bytes;
   return CQ_OK;
 }
 
@@ -174,7 +188,7 @@ int check_decode(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* k,
                  const cq_qtensor_t* v, const void* k_text_f16, const void* v_text_f16,
                  int32_t n_text, int32_t n_text_cap, bool length_on_device,
                  const cq_calib_t* calib, float softmax_scale, const void* out_f16,
-                 DecodeCall* call) {
+                 size_t scratch_limit, DecodeCall* call) {
   int rc = check_layout(L, true);
   if (rc != CQ_OK) return rc;
   if (!q_f16 || !out_f16) return fail(CQ_ERR_NULL, "q_f16 or out_f16 is NULL");
@@ -198,7 +212,7 @@ int check_decode(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* k,
   if (!std::isfinite(softmax_scale) || softmax_scale < 0.f)
     return fail(CQ_ERR_SHAPE, "softmax_scale must be finite and >= 0");
   call->softmax_scale = softmax_scale == 0.f ? 1.0f / std::sqrt((float)L->head_dim) : softmax_scale;
-  return select_kernels(L, n_text, n_text_cap, call);
+  return select_kernels(L, n_text, n_text_cap, scratch_limit, call);
 }
 
 int launch_decode(const DecodeCall& call, const void* q_f16, const cq_qtensor_t* k,
@@ -208,7 +222,11 @@ int launch_decode(const DecodeCall& call, const void* q_f16, const cq_qtensor_t*
   const cq_qtensor_t& kq = k ? *k : kNone;
   const cq_qtensor_t& vq = v ? *v : kNone;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const hipError_t e = call.tuned
+  const hipError_t e = call.streamed
+      ? cq::launch_decode_stream(call.shape, call.stream, q_f16, kq, vq, k_text_f16, v_text_f16,
+                                 n_text_dev, call.calib, call.softmax_scale, out_f16,
+                                 static_cast<float*>(workspace), st)
+      : call.tuned
       ? cq::launch_decode_fused(call.shape, call.plan, q_f16, kq, vq, k_text_f16, v_text_f16,
                                 n_text_dev, call.calib, call.softmax_scale, out_f16,
                                 static_cast<float*>(workspace), st)
@@ -294,7 +312,7 @@ size_t cq_decode_workspace_bytes(const cq_layout_t* L, int32_t n_text, const cq_
   cq::Calib c;
   if (check_layout(L, true) != CQ_OK || n_text < 0 || check_calib(calib, &c) != CQ_OK) return 0;
   DecodeCall call;
-  if (select_kernels(L, n_text, n_text, &call) != CQ_OK) return 0;
+  if (select_kernels(L, n_text, n_text, SIZE_MAX, &call) != CQ_OK) return 0;
   return call.ws_bytes;
 }
 
@@ -347,7 +365,7 @@ int cq_decode_attn(const cq_layout_t* L, const void* q_f16, const cq_qtensor_t* 
                    void* stream) {
   DecodeCall call;
   int rc = check_decode(L, q_f16, k, v, k_text_f16, v_text_f16, n_text, n_text_cap, false, calib,
-                        softmax_scale, out_f16, &call);
+                        softmax_scale, out_f16, SIZE_MAX, &call);
   if (rc != CQ_OK) return rc;
   if ((rc = check_workspace(workspace, workspace_bytes, call.ws_bytes)) != CQ_OK) return rc;
   return launch_decode(call, q_f16, k, v, k_text_f16, v_text_f16, nullptr, out_f16, workspace, stream);
@@ -359,7 +377,7 @@ int cq_decode_attn_noalloc(const cq_layout_t* L, const void* q_f16, const cq_qte
                            float softmax_scale, void* out_f16, void* stream) {
   DecodeCall call;
   int rc = check_decode(L, q_f16, k, v, k_text_f16, v_text_f16, n_text, n_text_cap, false, calib,
-                        softmax_scale, out_f16, &call);
+                        softmax_scale, out_f16, (size_t)CQ_NOALLOC_SCRATCH_BYTES, &call);
   if (rc != CQ_OK) return rc;
   if (call.ws_bytes > (size_t)CQ_NOALLOC_SCRATCH_BYTES)
     return fail(CQ_ERR_WORKSPACE,
@@ -381,7 +399,7 @@ int cq_decode_attn_devlen(const cq_layout_t* L, const void* q_f16, const cq_qten
     return fail(CQ_ERR_ALIGN, "n_text_dev must be 4-byte aligned");
   DecodeCall call;
   int rc = check_decode(L, q_f16, k, v, k_text_f16, v_text_f16, n_text_max, n_text_cap, true, calib,
-                        softmax_scale, out_f16, &call);
+                        softmax_scale, out_f16, SIZE_MAX, &call);
   if (rc != CQ_OK) return rc;
   if ((rc = check_workspace(workspace, workspace_bytes, call.ws_bytes)) != CQ_OK) return rc;
   return launch_decode(call, q_f16, k, v, k_text_f16, v_text_f16, n_text_dev, out_f16, workspace,

@@ -137,6 +137,25 @@ hipError_t launch_decode_fused(const DecodeShape& s, const FusedPlan& plan, cons
                                float softmax_scale, void* out, float* workspace,
                                hipStream_t stream);
 
+// Streaming decode for split rows (decode_stream.hip): logits pass (all query heads of a KV head
+// per workgroup, raw logits and chunk extrema to the workspace), values pass, combine.  Takes 1- and
+// 2-bit codes, keys in groups of 128 tokens, token-wise values, up to 8 query heads per KV head.
+struct StreamPlan {
+  bool ok = false;
+  int ca = 1, cb = 1;              // chunks per row of the logits pass / of the values pass
+  int ct = 0;                      // chunks per row of the fp16 tail (values pass)
+  size_t ws_lref_floats = 0;       // workspace: [extrema | group references | logits | partials],
+  size_t ws_logits_floats = 0;     // offsets in floats
+  size_t ws_partial_floats = 0;
+  size_t ws_bytes = 256;
+};
+StreamPlan make_stream_plan(const DecodeShape& s, int min_chunks);
+hipError_t launch_decode_stream(const DecodeShape& s, const StreamPlan& plan, const void* q,
+                                const cq_qtensor_t& k, const cq_qtensor_t& v, const void* k_text,
+                                const void* v_text, const int32_t* n_text_dev, const Calib& calib,
+                                float softmax_scale, void* out, float* workspace,
+                                hipStream_t stream);
+
 }  // namespace cq
 
 #endif  // CQ_INTERNAL_H_

@@ -208,35 +208,27 @@ __global__ void combine_kernel(int n_chunks, int d, const float* __restrict__ pa
   const size_t hq = blockIdx.x;
   const int c = threadIdx.x;
   const float* base = partial + hq * n_chunks * (size_t)(d + 2);
-  // One pass, four chunks at a time: their twelve loads are independent of the running
-  // (M, num, den) and go out together, so the kernel waits for memory once per four chunks
-  // instead of twice per chunk.
-  float M = -FLT_MAX, num = 0.f, den = 0.f;
-  for (int i0 = 0; i0 < n_chunks; i0 += 4) {
-    float m[4], l[4], acc[4];
+  // Two passes, neither with a chain through memory: first the common reference point M (every
+  // thread reads the same few m's), then eight chunks at a time, whose loads are independent of
+  // each other and of the running sums.  A chunk without tokens has m = -FLT_MAX and weight 0.
+  float M = -FLT_MAX;
+  for (int i = 0; i < n_chunks; ++i) M = fmaxf(M, base[(size_t)i * (d + 2)]);
+  float num = 0.f, den = 0.f;
+  for (int i0 = 0; i0 < n_chunks; i0 += 8) {
+    float m[8], l[8], acc[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < 8; ++u) {
       const float* pi = base + (size_t)min(i0 + u, n_chunks - 1) * (d + 2);
       m[u] = pi[0];
       l[u] = pi[1];
       acc[u] = pi[2 + c];
     }
-    float Mn = M;
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (i0 + u < n_chunks) Mn = fmaxf(Mn, m[u]);
-    const float keep = expf(M - Mn);          // 0 on the first pass (M = -FLT_MAX)
-    num *= keep;
-    den *= keep;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (i0 + u < n_chunks) {
-        const float w = expf(m[u] - Mn);
-        num = fmaf(w, acc[u], num);
-        den = fmaf(w, l[u], den);
-      }
+    for (int u = 0; u < 8; ++u) {
+      const float w = i0 + u < n_chunks ? expf(m[u] - M) : 0.f;
+      num = fmaf(w, acc[u], num);
+      den = fmaf(w, l[u], den);
     }
-    M = Mn;
   }
   out[hq * d + c] = __float2half_rn(num / den);
 }
