@@ -208,23 +208,29 @@ __global__ void combine_kernel(int n_chunks, int d, const float* __restrict__ pa
   const size_t hq = blockIdx.x;
   const int c = threadIdx.x;
   const float* base = partial + hq * n_chunks * (size_t)(d + 2);
-  // Two passes, neither with a chain through memory: first the common reference point M (every
-  // thread reads the same few m's), then eight chunks at a time, whose loads are independent of
-  // each other and of the running sums.  A chunk without tokens has m = -FLT_MAX and weight 0.
-  float M = -FLT_MAX;
-  for (int i = 0; i < n_chunks; ++i) M = fmaxf(M, base[(size_t)i * (d + 2)]);
-  float num = 0.f, den = 0.f;
-  for (int i0 = 0; i0 < n_chunks; i0 += 8) {
-    float m[8], l[8], acc[8];
+  // Sixteen chunks at a time, all of their loads independent of each other and of the running
+  // sums: with up to 16 chunks a thread waits for memory once.  Each batch brings its own
+  // reference point; the sums so far are rescaled when it is larger (online softmax over batches).
+  // A chunk without tokens has m = -FLT_MAX and weight 0.
+  float M = -FLT_MAX, num = 0.f, den = 0.f;
+  for (int i0 = 0; i0 < n_chunks; i0 += 16) {
+    float m[16], l[16], acc[16];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < 16; ++u) {
       const float* pi = base + (size_t)min(i0 + u, n_chunks - 1) * (d + 2);
       m[u] = pi[0];
       l[u] = pi[1];
       acc[u] = pi[2 + c];
     }
+    float Mb = M;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < 16; ++u) Mb = fmaxf(Mb, m[u]);       // a repeated (clamped) chunk changes nothing
+    const float keep = expf(M - Mb);                          // 1 when the reference stays, 0 at the start
+    num *= keep;
+    den *= keep;
+    M = Mb;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
       const float w = i0 + u < n_chunks ? expf(m[u] - M) : 0.f;
       num = fmaf(w, acc[u], num);
       den = fmaf(w, l[u], den);

@@ -662,7 +662,12 @@ def _all_rows_check(w, bits, what):
     for name, dev_t, axis, group in (("k", k_dev, O.AXIS_CHANNEL, 128), ("v", v_dev, O.AXIS_TOKEN, 128)):
         ref_t = ON.quantize_tensor(x[name].cpu().numpy(), bits, axis, group)
         del x[name]
-        assert np.array_equal(H.words_of(dev_t.codes), ref_t["words"]), "%s %s codes" % (what, name)
+        got = H.words_of(dev_t.codes)
+        if not np.array_equal(got, ref_t["words"]):
+            bad = np.argwhere(got != ref_t["words"])
+            first = tuple(int(i) for i in bad[0])
+            raise AssertionError("%s %s codes: %d words differ, first at %s (%08x, oracle %08x), last at %s" % (
+                what, name, len(bad), first, got[first], ref_t["words"][first], bad[-1].tolist()))
         assert np.array_equal(dev_t.scale.cpu().numpy().view(np.uint32), ref_t["scale"].view(np.uint32))
         assert np.array_equal(dev_t.min.cpu().numpy().view(np.uint16), ref_t["min"].view(np.uint16))
         refs[name] = ref_t
