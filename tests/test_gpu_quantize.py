@@ -201,30 +201,6 @@ def test_full_size_quantizer_config_on_sampled_rows(kernel_path, bits, group):
 
 
 @pytest.mark.tuned_only
-def test_full_size_quantizer_config_every_row(kernel_path):
-    """configs[3] at full size, b = 1, groups of 128: all 1024 (batch, KV head) rows of both
-    tensors (2 x 2.1 G elements) against the C++ oracle twin (tied to the numpy oracle by CPU
-    tests), bit for bit, one tensor at a time to bound host memory."""
-    from oracle import cq_oracle_native as ON
-    w = synth.WORKLOADS[3]
-    lay = H.layout_of(w, 1, 128, 128)
-    x = synth.make_inputs(w, "cuda", parts=("k", "v"))
-    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
-    try:
-        k_out, v_out = cq.cq_quantize_kv(lay, x["k"], x["v"])
-        torch.cuda.synchronize()
-    finally:
-        cq.cq_bench_set_kernel_path(prev)
-    for name, out, axis in (("k", k_out, lay.k_axis), ("v", v_out, lay.v_axis)):
-        host = x[name].cpu().numpy()
-        del x[name]
-        ref = ON.quantize_tensor(host, 1, axis, 128)
-        del host
-        H.assert_qtensor_equal(out, ref, "configs[3] all rows, %s" % name)
-        del ref
-
-
-@pytest.mark.tuned_only
 @pytest.mark.parametrize("bits", [4, 8])
 def test_wide_codes_round_exact_ties_to_even_on_the_tuned_path(kernel_path, bits):
     """Every code boundary of a 4- or 8-bit grid hit exactly: values k + 1/2 steps of a group
