@@ -203,7 +203,7 @@ __global__ void __launch_bounds__(kAThreads) __attribute__((amdgpu_waves_per_eu(
     const float s0 = s01[slot][0], s1 = s01[slot][1];
     const float smax = wave_max_nonneg(fmaxf(s0, s1));
     v4i A0[NS], A1[NS];
-    float bias_h[NS], inv_f[NS], inv_f16[NS];
+    float bias_h[NS], inv_f[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const int F = fixed_point_shift(qmax[s] * smax);
@@ -215,7 +215,6 @@ __global__ void __launch_bounds__(kAThreads) __attribute__((amdgpu_waves_per_eu(
         x1[h] = product_digits(qv1[s][h], s1f);
       }
       inv_f[s] = ldexpf(1.f, -F);
-      inv_f16[s] = ldexpf(1.f, 16 - F);
       uint8_t* xb = stage + s * 2048;
       __builtin_amdgcn_wave_barrier();
       *reinterpret_cast<v4i*>(xb + x_wr0) = x0;
@@ -257,15 +256,19 @@ __global__ void __launch_bounds__(kAThreads) __attribute__((amdgpu_waves_per_eu(
         }
       }
     };
-    float sv[NS][TILES], gmn[NS], gmx[NS];       // the group's logits of this lane, their extrema
+    // The group's logits of this lane stay in units of 2^-F until the group is done: u = the
+    // integer the digit accumulators spell, logit = u * 2^-F + bias.  Scale and bias are the same
+    // for every token of the group and head and the scale is positive, so extrema and distances
+    // are taken on u and converted once.
+    float sv[NS][TILES], gmn[NS], gmx[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) { gmn[s] = FLT_MAX; gmx[s] = -FLT_MAX; }
     auto finish_tile = [&](int s, int tile, const v4i& c) {
       const int lo = c[0] + (c[1] << 8), hi = c[2] + (c[3] << 8);
-      const float v = fmaf((float)hi, inv_f16[s], fmaf((float)lo, inv_f[s], bias_h[s]));
-      sv[s][tile] = v;
-      gmn[s] = fminf(gmn[s], v);
-      gmx[s] = fmaxf(gmx[s], v);
+      const float u = fmaf((float)hi, 65536.f, (float)lo);
+      sv[s][tile] = u;
+      gmn[s] = fminf(gmn[s], u);
+      gmx[s] = fmaxf(gmx[s], u);
     };
 #pragma unroll
     for (int tile = 0; tile < TILES; tile += 2) {
@@ -296,14 +299,17 @@ __global__ void __launch_bounds__(kAThreads) __attribute__((amdgpu_waves_per_eu(
     // calibration line) and the fp16 distances to it, two tokens per store
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      mn[s] = fminf(mn[s], gmn[s]);
-      mx[s] = fmaxf(mx[s], gmx[s]);
-      const float ref = a.falling ? row_min(gmn[s]) : row_max(gmx[s]);
+      mn[s] = fminf(mn[s], fmaf(gmn[s], inv_f[s], bias_h[s]));
+      mx[s] = fmaxf(mx[s], fmaf(gmx[s], inv_f[s], bias_h[s]));
+      const float ref_u = a.falling ? row_min(gmn[s]) : row_max(gmx[s]);
+      const float ref = fmaf(ref_u, inv_f[s], bias_h[s]);
       __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, ref), rbuf, r_off[s], t * 4, 0);
+      // distance e = |ref_u - u| 2^-F = k u - k ref_u with k = -+2^-F
+      const float k = a.falling ? inv_f[s] : -inv_f[s];
+      const float c0 = -k * ref_u;
 #pragma unroll
       for (int pr = 0; pr < TILES / 2; ++pr) {
-        // |ref - s| is the distance for either kind of reference
-        const v2h16 e = {(_Float16)fabsf(ref - sv[s][pr]), (_Float16)fabsf(ref - sv[s][pr + 4])};
+        const v2h16 e = {(_Float16)fmaf(sv[s][pr], k, c0), (_Float16)fmaf(sv[s][pr + 4], k, c0)};
         __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, e), lbuf, l_off[s],
                                               (t * 128 + pr * 32) * 2, 0);
       }
@@ -360,11 +366,15 @@ __global__ void __launch_bounds__(kAThreads) __attribute__((amdgpu_waves_per_eu(
 
 // ===================================================================================== values pass
 // SPW = head sets per visual wave: NS (one wave carries all the workgroup's heads) or 1 with NS = 2
-// (the visual waves are split between the two sets).
-template <int BITS, int NS, int SPW>
+// (the visual waves are split between the two sets).  HL = heads that exist in the last set
+// (g - 4 (NS - 1)) where a wave carries every set, so that the weights of head slots without a
+// head are not computed at all; 4 (all slots treated alike) where the sets are split over waves.
+template <int BITS, int NS, int SPW, int HL>
 __global__ void __launch_bounds__(kBThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
 stream_values_kernel(const StreamArgs a) {
+  static_assert(HL >= 1 && HL <= kHeads && (SPW == NS || HL == kHeads), "see above");
   constexpr int NH = NS * kHeads;                // head slots of the workgroup
+  constexpr int kSlots = kHeads * (SPW - 1) + HL;          // head slots of a visual wave that hold a head
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n16 = lane & 15, kb = lane >> 4;
   // workgroup = (row, chunk of the fp16 tail) for the first n_text_wg of them, then (row, chunk of
@@ -531,7 +541,7 @@ stream_values_kernel(const StreamArgs a) {
     auto load_logits = [&](uint32_t (&dst)[WH], int k) {     // group k of the wave
       const int w0 = group_of(k) * 64 + lane;
 #pragma unroll
-      for (int j = 0; j < WH; ++j) dst[j] = stream_load<true>(lg_row[j] + w0);
+      for (int j = 0; j < kSlots; ++j) dst[j] = stream_load<true>(lg_row[j] + w0);
     };
     auto prep_tile = [&](int T, const uint32_t (&lg)[WH], int k) {   // tile T of the wave's group k
       if (__builtin_amdgcn_ballot_w64(vsr[T] >= fit_below) != 0) {
@@ -552,6 +562,7 @@ stream_values_kernel(const StreamArgs a) {
 #pragma unroll
         for (int i = 0; i < kHeads; ++i) {
           const int j = 4 * s + i;
+          if (j >= kSlots) { xs[s][i] = 0; continue; }     // no such head: zero digits, nothing summed
           const uint32_t pairw = lg[j];
           const float e = __half2float(__ushort_as_half((uint16_t)(T ? pairw >> 16 : pairw & 0xffffu)));
           const float p = __builtin_amdgcn_exp2f(fmaf(e, na2[j], cc[i]));
@@ -589,7 +600,7 @@ stream_values_kernel(const StreamArgs a) {
         if (prep_next) prep_tile(0, lg_next, k + 1);
         // the next group becomes the current one; its successor's distances are asked for
 #pragma unroll
-        for (int j = 0; j < WH; ++j) lg_cur[j] = lg_next[j];
+        for (int j = 0; j < kSlots; ++j) lg_cur[j] = lg_next[j];
       }
       pin_order();
       load_codes(T ^ 1, 2 * k + T + 3);
@@ -1010,22 +1021,46 @@ hipError_t launch_decode_stream(const DecodeShape& s, const StreamPlan& plan, co
       blocks_a > 0x7fffffffu || blocks_b > 0x7fffffffu)
     return hipErrorInvalidConfiguration;
   const int ns = s.g > kHeads ? 2 : 1;
+  const int hl = s.g - kHeads * (ns - 1);        // heads of the last set
   void (*kern_a)(const StreamArgs) = nullptr;
   void (*kern_b)(const StreamArgs) = nullptr;
   int slot = 0;
+  auto values_kernel = [hl](auto bits, auto sets) -> void (*)(const StreamArgs) {
+    constexpr int B = decltype(bits)::value, S = decltype(sets)::value;
+    switch (hl) {
+      case 1: return stream_values_kernel<B, S, S, 1>;
+      case 2: return stream_values_kernel<B, S, S, 2>;
+      case 3: return stream_values_kernel<B, S, S, 3>;
+      default: return stream_values_kernel<B, S, S, 4>;
+    }
+  };
+  using std::integral_constant;
   switch (s.bits * 2 + ns) {
-    case 1 * 2 + 1: kern_a = stream_logits_kernel<1, 1>; kern_b = stream_values_kernel<1, 1, 1>; slot = 0; break;
-    case 1 * 2 + 2: kern_a = stream_logits_kernel<1, 2>; kern_b = stream_values_kernel<1, 2, 2>; slot = 1; break;
-    case 2 * 2 + 1: kern_a = stream_logits_kernel<2, 1>; kern_b = stream_values_kernel<2, 1, 1>; slot = 2; break;
+    case 1 * 2 + 1:
+      kern_a = stream_logits_kernel<1, 1>;
+      kern_b = values_kernel(integral_constant<int, 1>{}, integral_constant<int, 1>{});
+      slot = 0;
+      break;
+    case 1 * 2 + 2:
+      kern_a = stream_logits_kernel<1, 2>;
+      kern_b = values_kernel(integral_constant<int, 1>{}, integral_constant<int, 2>{});
+      slot = 4;
+      break;
+    case 2 * 2 + 1:
+      kern_a = stream_logits_kernel<2, 1>;
+      kern_b = values_kernel(integral_constant<int, 2>{}, integral_constant<int, 1>{});
+      slot = 8;
+      break;
     // two-bit codes with two head sets: both sets in one wave would spill (twice the code
     // registers), so the visual waves are split between the sets
-    case 2 * 2 + 2: kern_a = stream_logits_kernel<2, 2>; kern_b = stream_values_kernel<2, 2, 1>; slot = 3; break;
+    case 2 * 2 + 2: kern_a = stream_logits_kernel<2, 2>; kern_b = stream_values_kernel<2, 2, 1, 4>; slot = 12; break;
     default: return hipErrorInvalidValue;
   }
+  if (!(s.bits == 2 && ns == 2)) slot += hl - 1;
   const size_t lds_a = stream_logits_lds(ns), lds_b = stream_values_lds(ns, tstride, a.ref_stride);
   if (lds_b > 160 * 1024) return hipErrorInvalidConfiguration;
   // the values kernel's dynamic LDS limit is raised once per (device, kernel) and only ever grows
-  static std::atomic<size_t> configured[kMaxDevices][4];
+  static std::atomic<size_t> configured[kMaxDevices][13];
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
