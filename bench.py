@@ -65,6 +65,7 @@ def main() -> int:
     ap.add_argument("--no-fp16-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="override the batch (debugging only)")
     ap.add_argument("--n-vis", type=int, default=0, help="override the visual tokens (debugging only)")
+    ap.add_argument("--q-heads", type=int, default=0, help="override the query heads (debugging only)")
     ap.add_argument("--n-text", type=int, default=-1, help="override the text tokens (debugging only)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -93,6 +94,8 @@ def main() -> int:
         w = w.replace(batch=args.batch)
     if args.n_vis:
         w = w.replace(n_vis=args.n_vis)
+    if args.q_heads:
+        w = w.replace(n_q_heads=args.q_heads)
     if args.n_text >= 0:
         w = w.replace(n_text=args.n_text)
 
@@ -404,7 +407,7 @@ def main() -> int:
     # of two rocprofv3 --pmc runs of this command holds the figure together with the SHA-256 of the
     # kernel source it was taken on; it is reported only while that source is unchanged.
     traffic, traffic_source = None, None
-    if (fused and args.config == 2 and args.bits == 1 and args.group == 128 and not args.batch and not args.n_vis and args.n_text < 0
+    if (fused and args.config == 2 and args.bits == 1 and args.group == 128 and not args.batch and not args.n_vis and not args.q_heads and args.n_text < 0
             and args.v_axis == "token"):
         import hashlib
         prof = os.path.join("profiles", "fused_row_kernel_configs2_hbm_traffic.txt")

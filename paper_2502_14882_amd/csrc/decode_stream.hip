@@ -93,8 +93,10 @@ extern __shared__ __align__(16) uint8_t smem[];
 
 // ===================================================================================== logits pass
 // BITS = code width (1 or 2); NS = sets of 4 query heads (1 or 2: g <= 4 or g <= 8).
+// (one head set leaves room for four waves per SIMD, two need the registers of three)
 template <int BITS, int NS>
-__global__ void __launch_bounds__(kAThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) stream_logits_kernel(const StreamArgs a) {
+__global__ void __launch_bounds__(kAThreads) __attribute__((amdgpu_waves_per_eu(NS == 1 ? 4 : 3, NS == 1 ? 4 : 3)))
+stream_logits_kernel(const StreamArgs a) {
   constexpr int TILES = 8;                       // 16-token tiles per key group
   constexpr int kV = 8 / BITS, kCW = 32 / BITS;  // variants per byte, codes per word
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -370,7 +372,7 @@ __global__ void __launch_bounds__(kAThreads) __attribute__((amdgpu_waves_per_eu(
 // (g - 4 (NS - 1)) where a wave carries every set, so that the weights of head slots without a
 // head are not computed at all; 4 (all slots treated alike) where the sets are split over waves.
 template <int BITS, int NS, int SPW, int HL>
-__global__ void __launch_bounds__(kBThreads) __attribute__((amdgpu_waves_per_eu(3, 3)))
+__global__ void __launch_bounds__(kBThreads) __attribute__((amdgpu_waves_per_eu(NS == 1 ? 4 : 3, NS == 1 ? 4 : 3)))
 stream_values_kernel(const StreamArgs a) {
   static_assert(HL >= 1 && HL <= kHeads && (SPW == NS || HL == kHeads), "see above");
   constexpr int NH = NS * kHeads;                // head slots of the workgroup
@@ -955,10 +957,12 @@ StreamPlan make_stream_plan(const DecodeShape& s, int min_chunks) {
   // registers of 3 waves per SIMD), four with one; chunks of at least 8 key groups (2 per wave)
   const long long wg_per_cu = s.g > kHeads ? 3 : 4;
   p.ca = clamp((wg_per_cu * cus + rows - 1) / rows, 1, n_groups >= 8 ? n_groups / 8 : 1);
-  // values pass: workgroups of 4 waves, three resident per CU; chunks of at least 8 groups (2 per
+  // values pass: workgroups of 4 waves, as many resident per CU as in the logits pass (two-bit
+  // codes with the sets split over the waves would fit four as well and are 5 % slower that way:
+  // 110 against 105 us on the long-context configuration); chunks of at least 8 groups (2 per
   // wave).  The fp16 tail goes out in chunks of at least four 64-token blocks (one per wave): a
   // text wave is slow on its own (one stream of loads), so its workgroups must be short.
-  p.cb = clamp((3 * cus + rows - 1) / rows, 1, n_groups >= 8 ? n_groups / 8 : 1);
+  p.cb = clamp((wg_per_cu * cus + rows - 1) / rows, 1, n_groups >= 8 ? n_groups / 8 : 1);
   const int n_tblocks = (s.n_text + 63) / 64;
   p.ct = n_tblocks == 0 ? 0 : clamp(n_tblocks / 4, 1, 16);
   if (p.ca > 64) p.ca = 64;

@@ -311,6 +311,31 @@ def test_tuned_whole_sequence_statistics(kernel_path, bits, v_whole, decode_chun
 
 
 @pytest.mark.tuned_only
+@pytest.mark.parametrize("bits", [1, 2])
+@pytest.mark.parametrize("g", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_streaming_kernels_every_head_count(kernel_path, bits, g, decode_chunks):
+    """Split rows on the streaming kernels for 1 to 8 query heads per KV head: one or two head sets,
+    every count of heads in the last set (the values pass is compiled per count and skips the head
+    slots without a head), text tails that leave text waves idle, a ragged last chunk, the
+    calibration modes including a falling fixed line (references are then group minima)."""
+    decode_chunks(3)
+    w = synth.WORKLOADS[4].replace(batch=2, n_kv_heads=2, n_q_heads=2 * g, n_vis=128 * 13,
+                                   n_text=(0, 7, 70, 330)[g % 4], seed=8400 + 16 * bits + g)
+    c = Case(w, H.layout_of(w, bits))
+    prev = cq.cq_bench_set_kernel_path(cq.CQ_PATH_TUNED)
+    try:
+        dyn = cq.make_calib(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+        kept_logits = 2 * w.batch * w.n_q_heads * w.n_vis            # 16 bits per visual logit
+        assert cq.cq_decode_workspace_bytes(c.lay, w.n_text, dyn) > kept_logits    # the streaming plan
+        c.check(cq.CQ_CALIB_DYNAMIC, 1.0, 2.0)
+        c.check(cq.CQ_CALIB_NONE)
+        c.check(cq.CQ_CALIB_FIXED, 0.0, 30.0, gamma=-1.0, delta=1.0)
+        c.check(cq.CQ_CALIB_DYNAMIC, 2.0, 0.0, softmax_scale=0.05)
+    finally:
+        cq.cq_bench_set_kernel_path(prev)
+
+
+@pytest.mark.tuned_only
 @pytest.mark.parametrize("chunks", [2, 3])
 def test_tuned_channelwise_values_on_split_rows(kernel_path, chunks, decode_chunks):
     decode_chunks(chunks)
