@@ -91,6 +91,24 @@ struct StreamArgs {
 
 extern __shared__ __align__(16) uint8_t smem[];
 
+// Maximum / minimum over each row of 16 lanes, every lane gets the result.  Written out because
+// the compiler puts a canonicalising v_max in front of every fmaxf whose operand went through a
+// DPP move and then cannot fold the move into the maximum: three instructions per step instead of
+// one.  The inputs here are finite results of arithmetic.  (Two idle states separate a vector
+// write from a DPP read of the same register.)
+#define CQ_ROW_REDUCE(OP)                                                                        \
+  float r;                                                                                       \
+  asm volatile("s_nop 1\n\t" OP " %0, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t" \
+               "s_nop 1\n\t" OP " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t" \
+               "s_nop 1\n\t" OP " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\t"    \
+               "s_nop 1\n\t" OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf"               \
+               : "=&v"(r)                                                                        \
+               : "v"(v));                                                                        \
+  return r;
+__device__ __forceinline__ float row_max_finite(float v) { CQ_ROW_REDUCE("v_max_f32_dpp") }
+__device__ __forceinline__ float row_min_finite(float v) { CQ_ROW_REDUCE("v_min_f32_dpp") }
+#undef CQ_ROW_REDUCE
+
 // ===================================================================================== logits pass
 // BITS = code width (1 or 2); NS = sets of 4 query heads (1 or 2: g <= 4 or g <= 8).
 // (one head set leaves room for four waves per SIMD, two need the registers of three)
@@ -303,7 +321,7 @@ stream_logits_kernel(const StreamArgs a) {
     for (int s = 0; s < NS; ++s) {
       mn[s] = fminf(mn[s], fmaf(gmn[s], inv_f[s], bias_h[s]));
       mx[s] = fmaxf(mx[s], fmaf(gmx[s], inv_f[s], bias_h[s]));
-      const float ref_u = a.falling ? row_min(gmn[s]) : row_max(gmx[s]);
+      const float ref_u = a.falling ? row_min_finite(gmn[s]) : row_max_finite(gmx[s]);
       const float ref = fmaf(ref_u, inv_f[s], bias_h[s]);
       __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, ref), rbuf, r_off[s], t * 4, 0);
       // distance e = |ref_u - u| 2^-F = k u - k ref_u with k = -+2^-F
