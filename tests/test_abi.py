@@ -294,3 +294,14 @@ def test_binding_raises_when_library_is_missing(monkeypatch):
     monkeypatch.setattr(cq, "LIB_PATH", "/nonexistent/libcq.so")
     with pytest.raises(RuntimeError, match="not built"):
         cq.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it exits with a message before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
