@@ -232,13 +232,17 @@ def main() -> int:
         # region would book on its few steps.  At least MIN_SETTLE launches run untimed immediately
         # before the first event, without a synchronisation in between, so that the timed replays
         # are already queued behind work in flight and the clocks have settled.
-        MIN_TIMED, MIN_SETTLE = 1000, 200
+        # One recorded graph holds a whole number of K-step blocks, at least MIN_GRAPH launches:
+        # between two replays the device idles for ~7 us, which short graphs would book on their
+        # few steps (at K = 20 it added 0.4 us to every step).
+        MIN_TIMED, MIN_SETTLE, MIN_GRAPH = 1000, 200, 250
+        per_graph = args.steps * -(-MIN_GRAPH // args.steps)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            for i in range(args.steps):
+            for i in range(per_graph):
                 step(i)
-        n_timed = -(-MIN_TIMED // args.steps)
-        n_settle = -(-MIN_SETTLE // args.steps)
+        n_timed = -(-MIN_TIMED // per_graph)
+        n_settle = -(-MIN_SETTLE // per_graph)
         graph.replay()                      # untimed: instantiation and upload
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -251,15 +255,15 @@ def main() -> int:
         e1.record()
         torch.cuda.synchronize()
         wall_all_ms = (time.perf_counter() - t0) * 1e3
-        timed_launches = n_timed * args.steps
+        timed_launches = n_timed * per_graph
         mean_ms = e0.elapsed_time(e1) / timed_launches
         # host wall clock over settle + timed replays, per launch: an upper bound that also holds
         # the launch of the first replay
-        wall_ms = wall_all_ms / ((n_settle + n_timed) * args.steps)
+        wall_ms = wall_all_ms / ((n_settle + n_timed) * per_graph)
         # a replayed step must give what the eager step gives
-        last = sets[(args.steps - 1) % n_sets]
+        last = sets[(per_graph - 1) % n_sets]
         from_graph = last["out"].clone()
-        step(args.steps - 1)
+        step(per_graph - 1)
         torch.cuda.synchronize()
         if not torch.equal(from_graph, last["out"]):
             raise RuntimeError("graph replay and eager launch disagree")
@@ -452,8 +456,9 @@ def main() -> int:
                    "kernel_path": args.path, "min_chunks": args.chunks, "input_sets": n_sets},
         "launch": args.launch,
         "timed_region": {"launches_between_events": timed_launches,
-                         "note": "the graph of `steps` launches replayed back to back, preceded by "
-                                 ">= 200 untimed launches with no synchronisation in between"
+                         "note": "one graph of whole `steps`-blocks (>= 250 launches) replayed back to "
+                                 "back, preceded by >= 200 untimed launches with no synchronisation "
+                                 "in between"
                                  if args.launch == "graph" else "one call per step from Python",
                          "host_wall_ms_per_launch": wall_ms},
         "device_ms": {"mean_in_timed_region": mean_ms, "eager_median": med_ms, "eager_min": min_ms,
