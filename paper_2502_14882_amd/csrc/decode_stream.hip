@@ -13,7 +13,8 @@
 //                 query heads of the KV head at once: a second operand set for heads 4..7 reuses
 //                 the expanded code operands, which is most of the vector work.  Raw logits go to
 //                 the workspace in 16 bits (below), chunk extrema as [B*Hq][chunks][2].
-//   values pass   (row, chunk of 64-token tiles) per workgroup of 4 + 2 waves.  Every wave folds
+//   values pass   (row, chunk of key groups) per workgroup of 4 waves on the packed values, (row,
+//                 chunk of the fp16 tail) per workgroup of 4 text waves.  Every visual wave folds
 //                 the row's extrema, forms g (Sec. 3.2) and the reference point; the visual waves
 //                 read logits and packed values, exponentiate and accumulate the weighted value
 //                 sum on the int8 matrix cores (weights p_j * scale_j as base-256 digits, both head
@@ -385,16 +386,15 @@ stream_logits_kernel(const StreamArgs a) {
 }
 
 // ===================================================================================== values pass
-// SPW = head sets per visual wave: NS (one wave carries all the workgroup's heads) or 1 with NS = 2
-// (the visual waves are split between the two sets).  HL = heads that exist in the last set
-// (g - 4 (NS - 1)) where a wave carries every set, so that the weights of head slots without a
-// head are not computed at all; 4 (all slots treated alike) where the sets are split over waves.
-template <int BITS, int NS, int SPW, int HL>
+// HL = heads that exist in the last head set (g - 4 (NS - 1)): the weights of head slots without a
+// head are not computed at all.  ONE = one register slot for the packed values in flight instead
+// of two (with two head sets, where two slots spill).
+template <int BITS, int NS, int HL, bool ONE>
 __global__ void __launch_bounds__(kBThreads) __attribute__((amdgpu_waves_per_eu(NS == 1 ? 4 : 3, NS == 1 ? 4 : 3)))
 stream_values_kernel(const StreamArgs a) {
-  static_assert(HL >= 1 && HL <= kHeads && (SPW == NS || HL == kHeads), "see above");
+  static_assert(HL >= 1 && HL <= kHeads, "see above");
   constexpr int NH = NS * kHeads;                // head slots of the workgroup
-  constexpr int kSlots = kHeads * (SPW - 1) + HL;          // head slots of a visual wave that hold a head
+  constexpr int kSlots = kHeads * (NS - 1) + HL;           // head slots that hold a head
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n16 = lane & 15, kb = lane >> 4;
   // workgroup = (row, chunk of the fp16 tail) for the first n_text_wg of them, then (row, chunk of
@@ -421,7 +421,7 @@ stream_values_kernel(const StreamArgs a) {
 
   // ---- LDS: staging of the visual waves (weights as digits per head set, code bytes), the text
   // logits, every wave's partial sums for the epilogue, the chunk's table of group constants
-  constexpr int kStage = SPW * 1024 + 2048;
+  constexpr int kStage = NS * 1024 + 2048;
   uint8_t* stage = smem + (size_t)wave * kStage;
   float* tlog = reinterpret_cast<float*>(smem + kBVisWaves * kStage);          // [NH][tstride]
   uint8_t* tbytes = reinterpret_cast<uint8_t*>(tlog);
@@ -434,10 +434,7 @@ stream_values_kernel(const StreamArgs a) {
   // wave folds the row's chunk extrema of the logits pass itself: lane 16j + c takes chunks c,
   // c + 16, ... of head 4s + j.
   float a2[NH], c2v[NH];
-  constexpr int kSetWaves = kBVisWaves * SPW / NS;     // visual waves that share a head set's groups
-  constexpr bool kNT = SPW == NS;                // a second set reads the same values: keep them cached
-  const int vset = wave / kSetWaves, wsub = wave % kSetWaves;       // visual waves: set, index in it
-  const bool vis_work = vis_wave && wsub < n_gchunk;      // the wave owns at least one key group
+  const bool vis_work = vis_wave && wave < n_gchunk;      // the wave owns at least one key group
 #pragma unroll
   for (int s = 0; s < NS; ++s) {
     if (text_wg) {                               // nothing of this concerns the tail
@@ -471,7 +468,7 @@ stream_values_kernel(const StreamArgs a) {
       const float M = fmaxf(slope * (lo - gam) + shift, slope * (hi - gam) + shift);
       const bool exists = 4 * s + j < a.g;
       if (vis_wave && lane == 0)
-        mla[(wave * NH + 4 * s + j) * 3] = vis_work && (SPW == NS || s == vset) ? M : -FLT_MAX;
+        mla[(wave * NH + 4 * s + j) * 3] = vis_work ? M : -FLT_MAX;
       // exponent of a weight in base 2: a2 * s + c2v
       a2[4 * s + j] = exists ? slope * kLog2e : 0.f;
       c2v[4 * s + j] = exists ? (shift - slope * gam - M) * kLog2e : -200.f;   // no head: weight 0
@@ -502,35 +499,32 @@ stream_values_kernel(const StreamArgs a) {
   bool wrote = vis_work;       // this wave leaves partial sums in LDS (wave-uniform)
 
   if (vis_wave) {
-    // A visual wave works for SPW head sets at once (both sets against the same expanded value
-    // operands), or - SPW = 1 with two sets - for one of them, the workgroup's visual waves being
-    // split between the sets.  Pipeline over the wave's key groups (group k of the wave is group
-    // wsub + kSetWaves k of the chunk), two 64-token tiles each, tile u = 2k + T, as in the fused
+    // A visual wave works for all NS head sets at once (both sets against the same expanded value
+    // operands).  Pipeline over the wave's key groups (group k of the wave is group
+    // wave + kBVisWaves k of the chunk), two 64-token tiles each, tile u = 2k + T, as in the fused
     // kernel:
     //   G(u)  global loads of the tile's codes, scales and minima into a ring of two slots (slot T),
     //         and once per group of the stored logit distances of both tiles (one 4-byte load per
     //         head: the low half is tile 0's token `lane`, the high half tile 1's)
     //   P(u)  weights p = 2^(na2 e + c), their fixed-point digits X(u) and the code bytes to LDS
-    //   M(u)  transposing reads of X(u) (per set) and of the codes, 8 x (4 AND + SPW MFMA)
+    //   M(u)  transposing reads of X(u) (per set) and of the codes, 8 x (4 AND + NS MFMA)
     // One step runs M(u), P(u+1) and G(u+3); the distances are asked for two groups ahead.
-    constexpr int WH = SPW * kHeads;             // head slots of the wave
-    const int hs0 = kHeads * vset;               // first head slot of the wave
+    constexpr int WH = NH;                       // head slots of the wave
     float na2[WH];                               // wave-uniform: kept in scalar registers
 #pragma unroll
     for (int j = 0; j < WH; ++j) {
       float v = a2[j];
-      if constexpr (SPW < NS) v = vset == 1 ? a2[kHeads + j] : v;
       na2[j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v * dsign)));
     }
-    v4i acc[SPW][8];
-    float facc[SPW][8];
+    v4i acc[NS][8];
+    float facc[NS][8];
 #pragma unroll
-    for (int s = 0; s < SPW; ++s)
+    for (int s = 0; s < NS; ++s)
 #pragma unroll
       for (int p = 0; p < 8; ++p) { acc[s][p] = (v4i){0, 0, 0, 0}; facc[s][p] = 0.f; }
     int F_prep = 90, F_acc = 90, F_tile[2] = {90, 90};
     float fit_below = ldexpf(1.f, 29 - 90);      // scales below this fit the shift F_prep
-    const int n_my = wsub < n_gchunk ? (n_gchunk - wsub + kSetWaves - 1) / kSetWaves : 0;
+    const int n_my = wave < n_gchunk ? (n_gchunk - wave + kBVisWaves - 1) / kBVisWaves : 0;
     const size_t tok_row = (size_t)row * a.n_vis + (size_t)ga * 128;
     const uint32_t* vc_row = a.v_codes + tok_row * (4 * BITS);
     const float* vs_row = a.v_scale + tok_row;
@@ -538,25 +532,29 @@ stream_values_kernel(const StreamArgs a) {
     const uint32_t* lg_row[WH];                  // wave-uniform: a row's distances, two tokens per word
 #pragma unroll
     for (int j = 0; j < WH; ++j)
-      lg_row[j] = reinterpret_cast<const uint32_t*>(a.ws_logits + (head0 + min(hs0 + j, a.g - 1)) * (size_t)a.n_vis +
+      lg_row[j] = reinterpret_cast<const uint32_t*>(a.ws_logits + (head0 + min(j, a.g - 1)) * (size_t)a.n_vis +
                                                     (size_t)ga * 128);
     const int x_rd = kb * 256 + (n16 >> 1) * 16 + (n16 & 1) * 8;
     const int v_rd = (kb * 16 + (n16 >> 1)) * (16 * BITS) + (n16 & 1) * 8;
-    uint8_t* xbuf = stage;                        // [SPW][1024]: token lane -> 16 bytes (4 heads x 4 digits)
-    uint8_t* cbuf = stage + SPW * 1024;           // b = 1: two 1 KB buffers alternate; b = 2: one of 2 KB
-    v4i cg[2][BITS];
-    float vsr[2];
-    uint16_t vmr[2];
+    uint8_t* xbuf = stage;                        // [NS][1024]: token lane -> 16 bytes (4 heads x 4 digits)
+    uint8_t* cbuf = stage + NS * 1024;           // b = 1: two 1 KB buffers alternate; b = 2: one of 2 KB
+    // ONE: a single register slot for the tile in flight (loaded one tile ahead instead of two),
+    // where two would not fit the registers of three waves per SIMD
+    constexpr int kCodeSlots = ONE ? 1 : 2;
+    auto sl = [](int T) { return ONE ? 0 : T; };
+    v4i cg[kCodeSlots][BITS];
+    float vsr[kCodeSlots];
+    uint16_t vmr[kCodeSlots];
     // raw fp16 pairs of the current group of the wave and of the next one (converted where used)
     uint32_t lg_cur[WH], lg_next[WH];
-    auto group_of = [&](int k) { return wsub + kSetWaves * min(k, n_my - 1); };      // clamped
-    auto load_codes = [&](int T, int u) {        // tile u of the wave into slot T = u % 2
+    auto group_of = [&](int k) { return wave + kBVisWaves * min(k, n_my - 1); };      // clamped
+    auto load_codes = [&](int T, int u) {        // tile u of the wave (T = u % 2) into its slot
       const int j0 = (group_of(u >> 1) * 2 + T) * 64, j = j0 + lane;
 #pragma unroll
       for (int e = 0; e < BITS; ++e)
-        cg[T][e] = stream_load<kNT>(reinterpret_cast<const v4i*>(vc_row + (size_t)j0 * (4 * BITS) + 256 * e + 4 * lane));
-      vsr[T] = stream_load<kNT>(vs_row + j);
-      vmr[T] = stream_load<kNT>(vm_row + j);
+        cg[sl(T)][e] = stream_load<true>(reinterpret_cast<const v4i*>(vc_row + (size_t)j0 * (4 * BITS) + 256 * e + 4 * lane));
+      vsr[sl(T)] = stream_load<true>(vs_row + j);
+      vmr[sl(T)] = stream_load<true>(vm_row + j);
     };
     auto load_logits = [&](uint32_t (&dst)[WH], int k) {     // group k of the wave
       const int w0 = group_of(k) * 64 + lane;
@@ -564,21 +562,21 @@ stream_values_kernel(const StreamArgs a) {
       for (int j = 0; j < kSlots; ++j) dst[j] = stream_load<true>(lg_row[j] + w0);
     };
     auto prep_tile = [&](int T, const uint32_t (&lg)[WH], int k) {   // tile T of the wave's group k
-      if (__builtin_amdgcn_ballot_w64(vsr[T] >= fit_below) != 0) {
+      if (__builtin_amdgcn_ballot_w64(vsr[sl(T)] >= fit_below) != 0) {
         // some token's scale does not fit the running shift (rare after the first tiles)
-        F_prep = min(F_prep, fixed_point_shift(wave_max_nonneg(vsr[T])));
+        F_prep = min(F_prep, fixed_point_shift(wave_max_nonneg(vsr[sl(T)])));
         fit_below = ldexpf(1.f, 29 - F_prep);
       }
       F_tile[T] = F_prep;
-      const float vsf = ldexpf(vsr[T], F_prep);
-      float vmf = __half2float(__ushort_as_half(vmr[T]));
+      const float vsf = ldexpf(vsr[sl(T)], F_prep);
+      float vmf = __half2float(__ushort_as_half(vmr[sl(T)]));
       asm volatile("" : "+v"(vmf));
       const int gi = group_of(k);
-      v4i xs[SPW];
+      v4i xs[NS];
 #pragma unroll
-      for (int s = 0; s < SPW; ++s) {
+      for (int s = 0; s < NS; ++s) {
         // the group's constants of the set's four heads: one 16-byte LDS read (same address in all lanes)
-        const v4f cc = *reinterpret_cast<const v4f*>(ref_tab + gi * NH + hs0 + 4 * s);
+        const v4f cc = *reinterpret_cast<const v4f*>(ref_tab + gi * NH + 4 * s);
 #pragma unroll
         for (int i = 0; i < kHeads; ++i) {
           const int j = 4 * s + i;
@@ -593,16 +591,16 @@ stream_values_kernel(const StreamArgs a) {
       }
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int s = 0; s < SPW; ++s) *reinterpret_cast<v4i*>(xbuf + s * 1024 + 16 * lane) = xs[s];
+      for (int s = 0; s < NS; ++s) *reinterpret_cast<v4i*>(xbuf + s * 1024 + 16 * lane) = xs[s];
 #pragma unroll
       for (int e = 0; e < BITS; ++e)
-        *reinterpret_cast<v4i*>(cbuf + (BITS == 1 ? T * 1024 : 0) + 1024 * e + 16 * lane) = cg[T][e];
+        *reinterpret_cast<v4i*>(cbuf + (BITS == 1 ? T * 1024 : 0) + 1024 * e + 16 * lane) = cg[sl(T)][e];
     };
     // one step: M(tile u = 2k + T) with P(u + 1) and G(u + 3) in its shadow
     auto m_step = [&](int k, int T, bool prep_next) {
-      v4i A[SPW];
+      v4i A[NS];
 #pragma unroll
-      for (int s = 0; s < SPW; ++s) {
+      for (int s = 0; s < NS; ++s) {
         const uint8_t* xr = xbuf + s * 1024 + x_rd;
         const v2i a_lo = lds_read_tr8(xr), a_hi = lds_read_tr8(xr + 128);
         A[s] = (v4i){a_lo[0], a_lo[1], a_hi[0], a_hi[1]};
@@ -623,7 +621,8 @@ stream_values_kernel(const StreamArgs a) {
         for (int j = 0; j < kSlots; ++j) lg_cur[j] = lg_next[j];
       }
       pin_order();
-      load_codes(T ^ 1, 2 * k + T + 3);
+      if constexpr (ONE) load_codes(T, 2 * k + T + 2);        // the slot prep_tile has just emptied
+      else load_codes(T ^ 1, 2 * k + T + 3);
       if (T == 1) load_logits(lg_next, k + 2);
       pin_order();
       if (F_tile[T] < F_acc) {                    // wave-uniform, rare: a larger scale lowered the shift
@@ -631,7 +630,7 @@ stream_values_kernel(const StreamArgs a) {
         // cannot be shifted independently)
         const float w_old = ldexpf(1.f, -F_acc);
 #pragma unroll
-        for (int s = 0; s < SPW; ++s)
+        for (int s = 0; s < NS; ++s)
 #pragma unroll
           for (int p = 0; p < 8; ++p) {
             facc[s][p] = fmaf(digits_to_float(acc[s][p]), w_old, facc[s][p]);
@@ -653,20 +652,21 @@ stream_values_kernel(const StreamArgs a) {
         if (p < 7) Bn = variant_of(p + 1);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int s = 0; s < SPW; ++s)
+        for (int s = 0; s < NS; ++s)
           acc[s][p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[s], B, acc[s][p], 0, 0, 0);
       }
       lds_publish();
     };
     if (n_my > 0) {
       load_codes(0, 0);
-      load_codes(1, 1);
+      if constexpr (!ONE) load_codes(1, 1);
       load_logits(lg_cur, 0);
       load_logits(lg_next, 1);
       pin_order();
       prep_tile(0, lg_cur, 0);
       lds_publish();
-      load_codes(0, 2);
+      if constexpr (ONE) load_codes(1, 1);
+      else load_codes(0, 2);
       pin_order();
       int k = 0;
       for (; k + 1 < n_my; ++k) {                // no branch around a load or a preparation in here
@@ -678,14 +678,14 @@ stream_values_kernel(const StreamArgs a) {
       // the wave's sums: result lane (column n16 = code byte, head kb of each set), accumulator p
       const float inv_fv = ldexpf(1.f, -F_acc);
 #pragma unroll
-      for (int s = 0; s < SPW; ++s)
+      for (int s = 0; s < NS; ++s)
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
           const float v = fmaf(digits_to_float(acc[s][p]), inv_fv, facc[s][p]);
           constexpr int kV = 8 / BITS;
           const int tbyte = 16 * (p / kV) + n16;
           const int ch = (32 / BITS) * (tbyte >> 2) + code_in_word<BITS>(tbyte & 3, p % kV);
-          partial[(hs0 + 4 * s + kb) * kD + ch] = v * variant_weight<BITS>(p % kV);
+          partial[(4 * s + kb) * kD + ch] = v * variant_weight<BITS>(p % kV);
         }
     }
   } else {
@@ -883,27 +883,13 @@ stream_values_kernel(const StreamArgs a) {
     for (int i = lane; i < NH * kD; i += 64) partial[i] = 0.f;
   }
   // per-wave sums of the weights and of the additive value term (sum_j p_j min_j), per head
-  // (a visual wave that works for one of two sets kept its sums in slots 0..3)
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
     const float l = wave_sum(lsum[h]), m = wave_sum(msum[h]);
     if (lane == 0) {
-      if (!vis_wave) {
-        mla[(wave * NH + h) * 3 + 0] = wrote ? mref[h] : -FLT_MAX;
-        mla[(wave * NH + h) * 3 + 1] = l;
-        mla[(wave * NH + h) * 3 + 2] = m;
-      } else if (SPW == NS) {
-        mla[(wave * NH + h) * 3 + 1] = l;
-        mla[(wave * NH + h) * 3 + 2] = m;
-      } else {
-        if (h < kHeads) {
-          mla[(wave * NH + kHeads * vset + h) * 3 + 1] = l;
-          mla[(wave * NH + kHeads * vset + h) * 3 + 2] = m;
-        } else {                                   // the other set's slots
-          mla[(wave * NH + kHeads * (1 - vset) + h - kHeads) * 3 + 1] = 0.f;
-          mla[(wave * NH + kHeads * (1 - vset) + h - kHeads) * 3 + 2] = 0.f;
-        }
-      }
+      if (!vis_wave) mla[(wave * NH + h) * 3 + 0] = wrote ? mref[h] : -FLT_MAX;
+      mla[(wave * NH + h) * 3 + 1] = l;
+      mla[(wave * NH + h) * 3 + 2] = m;
     }
   }
   __syncthreads();
@@ -1049,11 +1035,14 @@ hipError_t launch_decode_stream(const DecodeShape& s, const StreamPlan& plan, co
   int slot = 0;
   auto values_kernel = [hl](auto bits, auto sets) -> void (*)(const StreamArgs) {
     constexpr int B = decltype(bits)::value, S = decltype(sets)::value;
+    // two head sets per wave: one register slot for the packed values in flight (no spills, and
+    // faster than two slots with spills at either code width)
+    constexpr bool kOne = S == 2;
     switch (hl) {
-      case 1: return stream_values_kernel<B, S, S, 1>;
-      case 2: return stream_values_kernel<B, S, S, 2>;
-      case 3: return stream_values_kernel<B, S, S, 3>;
-      default: return stream_values_kernel<B, S, S, 4>;
+      case 1: return stream_values_kernel<B, S, 1, kOne>;
+      case 2: return stream_values_kernel<B, S, 2, kOne>;
+      case 3: return stream_values_kernel<B, S, 3, kOne>;
+      default: return stream_values_kernel<B, S, 4, kOne>;
     }
   };
   using std::integral_constant;
@@ -1073,16 +1062,18 @@ hipError_t launch_decode_stream(const DecodeShape& s, const StreamPlan& plan, co
       kern_b = values_kernel(integral_constant<int, 2>{}, integral_constant<int, 1>{});
       slot = 8;
       break;
-    // two-bit codes with two head sets: both sets in one wave would spill (twice the code
-    // registers), so the visual waves are split between the sets
-    case 2 * 2 + 2: kern_a = stream_logits_kernel<2, 2>; kern_b = stream_values_kernel<2, 2, 1, 4>; slot = 12; break;
+    case 2 * 2 + 2:
+      kern_a = stream_logits_kernel<2, 2>;
+      kern_b = values_kernel(integral_constant<int, 2>{}, integral_constant<int, 2>{});
+      slot = 12;
+      break;
     default: return hipErrorInvalidValue;
   }
-  if (!(s.bits == 2 && ns == 2)) slot += hl - 1;
+  slot += hl - 1;
   const size_t lds_a = stream_logits_lds(ns), lds_b = stream_values_lds(ns, tstride, a.ref_stride);
   if (lds_b > 160 * 1024) return hipErrorInvalidConfiguration;
   // the values kernel's dynamic LDS limit is raised once per (device, kernel) and only ever grows
-  static std::atomic<size_t> configured[kMaxDevices][13];
+  static std::atomic<size_t> configured[kMaxDevices][16];
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
